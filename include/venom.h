@@ -1,0 +1,121 @@
+/*
+ * venom.h -- C ABI of the MI355X (gfx950) V:N:M sparse x dense product library.
+ *
+ * The operation is C = A . B with A (R x K, fp16) stored in the V:N:M format of the paper's
+ * section 3 ("The V:N:M format"), B dense K x C_cols fp16, fp32 accumulation (section 4,
+ * "Spatha").  N is always 2: the innermost pattern is the hardware's 2:4.
+ *
+ * Conventions that hold for every entry point
+ *   - every pointer named *_dev is DEVICE memory owned by the caller; the library never
+ *     allocates or frees device memory.  Pointers without that suffix are HOST memory.
+ *   - matrices are row-major; leading dimensions (lda, ldm, ldb, ldc) are in ELEMENTS.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - every call returns a venom_status_t; nothing aborts or throws across the boundary.
+ *   - a handle is a small HOST object holding NON-owning pointers into the caller's workspace;
+ *     it stays valid while that workspace is alive and unmodified.  venom_destroy frees the host
+ *     object only.
+ *
+ * Canonical V:N:M arrays (what venom_export returns and venom_import accepts), G = K / M:
+ *   values  uint16 [R][G][2]        fp16 bit patterns of the kept entries, 0x0000 in padded slots
+ *   columns uint16 [R/V][G][4]      column-loc: which 4 of the M columns each V x M block keeps,
+ *                                   relative ids in [0, M), strictly increasing
+ *   meta    uint32 [R][ceil(G/8)]   per (row, group) a nibble idx0 | idx1 << 2 with idx0 < idx1, the
+ *                                   two 2-bit m-indices, each addressing one of the block's 4
+ *                                   SELECTED columns; group g sits in bits [4(g%8), 4(g%8)+3] of
+ *                                   word g/8, unused nibbles are 0.
+ * Where the paper leaves a choice open the library follows these rules (the CPU oracle states
+ * the same ones): column-loc ascending; a block using fewer than 4 columns is padded with its
+ * smallest unused column ids; a (row, group) keeping fewer than 2 entries is padded with its
+ * smallest unused positions and stores +0 there; structure follows the mask, not the values.
+ */
+#ifndef VENOM_H_
+#define VENOM_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  VENOM_OK = 0,
+  VENOM_ERR_INVALID_ARG = 1, /* NULL where a pointer is required, negative size, bad enum value      */
+  VENOM_ERR_SHAPE = 2,       /* R % V, K % M, M < 4, V < 1, C_cols < 1, leading dimension too small  */
+  VENOM_ERR_UNSUPPORTED = 3, /* N != 2; misaligned pointer / leading dimension; shape the kernel does
+                                not cover (venom_spmm needs V % 32 == 0 and C_cols % 8 == 0)         */
+  VENOM_ERR_MASK_COLS = 4,   /* illegal mask: a V x M block uses more than 4 columns                 */
+  VENOM_ERR_MASK_ROW = 5,    /* illegal mask: a row keeps more than 2 entries in a group of M        */
+  VENOM_ERR_WORKSPACE = 6,   /* workspace NULL, misaligned (256 B) or smaller than required          */
+  VENOM_ERR_HIP = 7          /* a HIP runtime call or kernel launch failed                           */
+} venom_status_t;
+
+/* First offending block of an illegal mask, in row-major (block_row, group) order.  `row` is the
+ * first offending absolute row for VENOM_ERR_MASK_ROW and -1 for VENOM_ERR_MASK_COLS (a block
+ * that breaks both rules reports the column rule). */
+typedef struct {
+  int64_t block_row, group, row;
+} venom_violation_t;
+
+typedef struct venom_handle venom_handle_t;
+
+/* Bytes of device workspace a handle for an R x K matrix in V:2:M needs (canonical arrays, the
+ * kernel's packed copies and a status word).  Section 3 fixes the array shapes. */
+venom_status_t venom_workspace_bytes(int64_t R, int64_t K, int V, int N, int M, size_t* bytes);
+
+/* Section 3 / the sparsifier call of the paper's PyTorch integration listing: dense matrix plus
+ * mask -> values, column-loc, m-indices; checks that the mask is V:N:M-legal.
+ *   A_f16_dev   R x K fp16 (bit patterns are copied, never interpreted), lda >= K
+ *   mask_dev    R x K bytes, nonzero = keep, ldm >= K
+ *   workspace_dev / workspace_bytes   >= venom_workspace_bytes(...), 256-byte aligned
+ *   out         receives the handle on VENOM_OK, NULL otherwise
+ *   viol        optional (may be NULL); filled on VENOM_ERR_MASK_*
+ * Synchronises `stream` once (to read the legality word back). */
+venom_status_t venom_compress(const void* A_f16_dev, int64_t lda, const uint8_t* mask_dev, int64_t ldm,
+                              int64_t R, int64_t K, int V, int N, int M, void* workspace_dev,
+                              size_t workspace_bytes, void* stream, venom_handle_t** out,
+                              venom_violation_t* viol);
+
+/* Build a handle from canonical arrays already on the device (layout above).  The arrays are
+ * copied into the workspace; they are trusted to be well formed (indices in range). */
+venom_status_t venom_import(const uint16_t* values_dev, const uint16_t* columns_dev, const uint32_t* meta_dev,
+                            int64_t R, int64_t K, int V, int N, int M, void* workspace_dev,
+                            size_t workspace_bytes, void* stream, venom_handle_t** out);
+
+/* Copy the canonical arrays out (any of the three destinations may be NULL to skip it).
+ * Asynchronous on `stream`. */
+venom_status_t venom_export(const venom_handle_t* h, uint16_t* values_dev, uint16_t* columns_dev,
+                            uint32_t* meta_dev, void* stream);
+
+/* Section 3 read backwards: expand to the dense masked R x K fp16 matrix (+0 outside the
+ * structure), lda >= K.  Reads the KERNEL's packed copies, so it also checks the packing.
+ * Needs V % 32 == 0 (else VENOM_ERR_UNSUPPORTED).  Asynchronous on `stream`. */
+venom_status_t venom_decompress(const venom_handle_t* h, void* A_f16_dev, int64_t lda, void* stream);
+
+/* Section 4 (stages 1-3 of the kernel design; figure 4 for the mapping onto the 2:4 matrix
+ * instruction): C = A . B.
+ *   B_f16_dev   K x C_cols fp16, ldb >= C_cols
+ *   C_dev       R x C_cols, fp16 (c_dtype 0, rounded once from the fp32 accumulator, nearest-even)
+ *               or fp32 (c_dtype 1), ldc >= C_cols; must not overlap B
+ * B, C and both leading dimensions must be 16-byte aligned; V % 32 == 0; C_cols % 8 == 0.
+ * Asynchronous on `stream`, allocates nothing, bitwise repeatable (no atomics, no split K). */
+venom_status_t venom_spmm(const venom_handle_t* h, const void* B_f16_dev, int64_t ldb, int64_t C_cols,
+                          void* C_dev, int64_t ldc, int c_dtype, void* stream);
+
+/* Same product with an explicit kernel variant (tile shape / pipeline depth), for tuning sweeps.
+ * variant < 0 selects automatically as venom_spmm does; an unknown or unsuitable variant returns
+ * VENOM_ERR_UNSUPPORTED.  venom_spmm_variant_count() variants exist, numbered from 0. */
+venom_status_t venom_spmm_variant(const venom_handle_t* h, const void* B_f16_dev, int64_t ldb, int64_t C_cols,
+                                  void* C_dev, int64_t ldc, int c_dtype, int variant, void* stream);
+int venom_spmm_variant_count(void);
+/* Name of a variant ("v128_c256_w2x2", ...) or NULL. */
+const char* venom_spmm_variant_name(int variant);
+
+venom_status_t venom_get_info(const venom_handle_t* h, int64_t* R, int64_t* K, int* V, int* N, int* M);
+void venom_destroy(venom_handle_t* h);
+const char* venom_status_string(venom_status_t s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VENOM_H_ */

@@ -1,0 +1,219 @@
+"""ctypes binding of libvenom.so: argument marshalling only.
+
+Every step of the path (compression, packing, the product) runs in the library's HIP kernels;
+PyTorch supplies device memory and streams.  There is no CPU fallback: if the shared library has
+not been built, `lib()` raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, byref, c_char_p, c_int, c_int64, c_size_t, c_void_p
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libvenom.so")
+
+VENOM_OK = 0
+STATUS_NAMES = {
+    0: "VENOM_OK", 1: "VENOM_ERR_INVALID_ARG", 2: "VENOM_ERR_SHAPE", 3: "VENOM_ERR_UNSUPPORTED",
+    4: "VENOM_ERR_MASK_COLS", 5: "VENOM_ERR_MASK_ROW", 6: "VENOM_ERR_WORKSPACE", 7: "VENOM_ERR_HIP",
+}
+(VENOM_ERR_INVALID_ARG, VENOM_ERR_SHAPE, VENOM_ERR_UNSUPPORTED, VENOM_ERR_MASK_COLS, VENOM_ERR_MASK_ROW,
+ VENOM_ERR_WORKSPACE, VENOM_ERR_HIP) = range(1, 8)
+
+# every symbol include/venom.h declares
+EXPORTS = ("venom_workspace_bytes", "venom_compress", "venom_import", "venom_export", "venom_decompress",
+           "venom_spmm", "venom_spmm_variant", "venom_spmm_variant_count", "venom_spmm_variant_name",
+           "venom_get_info", "venom_destroy", "venom_status_string")
+
+
+class Violation(ctypes.Structure):
+    _fields_ = [("block_row", c_int64), ("group", c_int64), ("row", c_int64)]
+
+
+class VenomError(RuntimeError):
+    def __init__(self, status, where, violation=None):
+        self.status = status
+        self.violation = violation
+        msg = f"{where}: {STATUS_NAMES.get(status, status)}"
+        if violation is not None:
+            msg += f" at (block_row, group, row)={violation}"
+        super().__init__(msg)
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads the HIP library; raises if it is missing (there is no other implementation)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} not found: build it first (python -m paper_2310_02065_amd.build)")
+    L = ctypes.CDLL(LIB_PATH)
+    L.venom_workspace_bytes.argtypes = [c_int64, c_int64, c_int, c_int, c_int, POINTER(c_size_t)]
+    L.venom_compress.argtypes = [c_void_p, c_int64, c_void_p, c_int64, c_int64, c_int64, c_int, c_int, c_int,
+                                 c_void_p, c_size_t, c_void_p, POINTER(c_void_p), POINTER(Violation)]
+    L.venom_import.argtypes = [c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int, c_int, c_int, c_void_p,
+                               c_size_t, c_void_p, POINTER(c_void_p)]
+    L.venom_export.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    L.venom_decompress.argtypes = [c_void_p, c_void_p, c_int64, c_void_p]
+    L.venom_spmm.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_void_p, c_int64, c_int, c_void_p]
+    L.venom_spmm_variant.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_void_p, c_int64, c_int, c_int, c_void_p]
+    L.venom_spmm_variant_count.argtypes = []
+    L.venom_spmm_variant_name.argtypes = [c_int]
+    L.venom_spmm_variant_name.restype = c_char_p
+    L.venom_get_info.argtypes = [c_void_p, POINTER(c_int64), POINTER(c_int64), POINTER(c_int), POINTER(c_int),
+                                 POINTER(c_int)]
+    L.venom_destroy.argtypes = [c_void_p]
+    L.venom_destroy.restype = None
+    L.venom_status_string.argtypes = [c_int]
+    L.venom_status_string.restype = c_char_p
+    for name in ("venom_workspace_bytes", "venom_compress", "venom_import", "venom_export", "venom_decompress",
+                 "venom_spmm", "venom_spmm_variant", "venom_spmm_variant_count", "venom_get_info"):
+        getattr(L, name).restype = c_int
+    _lib = L
+    return L
+
+
+def _stream_ptr(stream=None):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return c_void_p(s.cuda_stream)
+
+
+def _ptr(t):
+    return c_void_p(t.data_ptr()) if t is not None else c_void_p(0)
+
+
+def venom_workspace_bytes(R, K, V, N, M) -> int:
+    n = c_size_t(0)
+    st = lib().venom_workspace_bytes(R, K, V, N, M, byref(n))
+    if st != VENOM_OK:
+        raise VenomError(st, "venom_workspace_bytes")
+    return n.value
+
+
+class Handle:
+    """Owns the workspace tensor and the host-side handle of one compressed matrix."""
+
+    def __init__(self, ptr, workspace, R, K, V, N, M):
+        self.ptr, self.workspace = ptr, workspace
+        self.R, self.K, self.V, self.N, self.M = R, K, V, N, M
+
+    @property
+    def G(self):
+        return self.K // self.M
+
+    def close(self):
+        if self.ptr:
+            lib().venom_destroy(self.ptr)
+            self.ptr = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def _workspace(R, K, V, N, M, device):
+    import torch
+    nbytes = venom_workspace_bytes(R, K, V, N, M)
+    ws = torch.empty(max(nbytes, 256) + 256, dtype=torch.uint8, device=device)
+    off = (-ws.data_ptr()) % 256
+    return ws, ws[off:off + max(nbytes, 256)], nbytes
+
+
+def venom_compress(A, mask, V, N, M, stream=None) -> Handle:
+    """A: R x K float16 CUDA tensor (row stride lda), mask: R x K uint8 CUDA tensor."""
+    import torch
+    assert A.is_cuda and mask.is_cuda and A.dtype == torch.float16 and mask.dtype in (torch.uint8, torch.bool)
+    assert A.dim() == 2 and mask.shape == A.shape and A.stride(1) == 1 and mask.stride(1) == 1
+    R, K = A.shape
+    ws_owner, ws, nbytes = _workspace(R, K, V, N, M, A.device)
+    out = c_void_p(0)
+    viol = Violation(-1, -1, -1)
+    st = lib().venom_compress(_ptr(A), A.stride(0) if R > 1 else max(K, A.stride(0)), _ptr(mask),
+                              mask.stride(0) if R > 1 else max(K, mask.stride(0)), R, K, V, N, M, _ptr(ws), nbytes,
+                              _stream_ptr(stream), byref(out), byref(viol))
+    if st != VENOM_OK:
+        v = (viol.block_row, viol.group, viol.row) if st in (VENOM_ERR_MASK_COLS, VENOM_ERR_MASK_ROW) else None
+        raise VenomError(st, "venom_compress", v)
+    h = Handle(out, ws, R, K, V, N, M)
+    h._owner = ws_owner
+    return h
+
+
+def venom_import(values, columns, meta, R, K, V, N, M, stream=None) -> Handle:
+    ws_owner, ws, nbytes = _workspace(R, K, V, N, M, values.device)
+    out = c_void_p(0)
+    st = lib().venom_import(_ptr(values), _ptr(columns), _ptr(meta), R, K, V, N, M, _ptr(ws), nbytes,
+                            _stream_ptr(stream), byref(out))
+    if st != VENOM_OK:
+        raise VenomError(st, "venom_import")
+    h = Handle(out, ws, R, K, V, N, M)
+    h._owner = ws_owner
+    return h
+
+
+def venom_export(h: Handle, stream=None):
+    """Returns (values int16 [R,G,2], columns int16 [R/V,G,4], meta int32 [R,ceil(G/8)]) CUDA tensors
+    holding the canonical uint16 / uint32 bit patterns."""
+    import torch
+    G = h.G
+    dev = h.workspace.device
+    values = torch.empty((h.R, G, 2), dtype=torch.int16, device=dev)
+    columns = torch.empty((h.R // h.V, G, 4), dtype=torch.int16, device=dev)
+    meta = torch.empty((h.R, (G + 7) // 8), dtype=torch.int32, device=dev)
+    st = lib().venom_export(h.ptr, _ptr(values), _ptr(columns), _ptr(meta), _stream_ptr(stream))
+    if st != VENOM_OK:
+        raise VenomError(st, "venom_export")
+    return values, columns, meta
+
+
+def venom_decompress(h: Handle, out=None, stream=None):
+    import torch
+    if out is None:
+        out = torch.empty((h.R, h.K), dtype=torch.float16, device=h.workspace.device)
+    st = lib().venom_decompress(h.ptr, _ptr(out), out.stride(0) if h.R > 1 else max(h.K, out.stride(0)),
+                                _stream_ptr(stream))
+    if st != VENOM_OK:
+        raise VenomError(st, "venom_decompress")
+    return out
+
+
+def venom_spmm(h: Handle, B, out=None, out_dtype=None, variant=-1, stream=None):
+    """C = A . B.  B: K x C float16 CUDA tensor (unit column stride); returns/fills C (R x C)."""
+    import torch
+    assert B.is_cuda and B.dtype == torch.float16 and B.dim() == 2 and B.stride(1) == 1
+    Ccols = B.shape[1]
+    if out is None:
+        out = torch.empty((h.R, Ccols), dtype=out_dtype or torch.float16, device=B.device)
+    assert out.dtype in (torch.float16, torch.float32) and out.stride(1) == 1
+    c_dtype = 1 if out.dtype == torch.float32 else 0
+    ldb = B.stride(0) if B.shape[0] > 1 else max(Ccols, B.stride(0))
+    ldc = out.stride(0) if out.shape[0] > 1 else max(Ccols, out.stride(0))
+    st = lib().venom_spmm_variant(h.ptr, _ptr(B), ldb, Ccols, _ptr(out), ldc, c_dtype, variant, _stream_ptr(stream))
+    if st != VENOM_OK:
+        raise VenomError(st, "venom_spmm")
+    return out
+
+
+def venom_get_info(h: Handle):
+    R, K = c_int64(), c_int64()
+    V, N, M = c_int(), c_int(), c_int()
+    st = lib().venom_get_info(h.ptr, byref(R), byref(K), byref(V), byref(N), byref(M))
+    if st != VENOM_OK:
+        raise VenomError(st, "venom_get_info")
+    return R.value, K.value, V.value, N.value, M.value
+
+
+def venom_spmm_variants():
+    L = lib()
+    return [L.venom_spmm_variant_name(i).decode() for i in range(L.venom_spmm_variant_count())]
+
+
+def venom_status_string(status: int) -> str:
+    return lib().venom_status_string(status).decode()

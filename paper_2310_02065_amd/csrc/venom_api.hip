@@ -1,0 +1,189 @@
+// The C ABI: argument validation, workspace carving, handle lifetime.  All device work is in
+// venom_format.hip / venom_spmm.hip; nothing here allocates device memory.
+#include <new>
+
+#include "venom_internal.h"
+
+using venom::Layout;
+
+namespace {
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+venom_status_t check_shape(int64_t R, int64_t K, int V, int N, int M) {
+  if (R < 0 || K < 0) return VENOM_ERR_INVALID_ARG;
+  if (N != 2) return VENOM_ERR_UNSUPPORTED;
+  if (V < 1 || M < venom::kSelCols) return VENOM_ERR_SHAPE;
+  if (R % V != 0 || K % M != 0) return VENOM_ERR_SHAPE;
+  if (M > 1024 || V >= (1 << 23)) return VENOM_ERR_UNSUPPORTED;
+  if (K >= ((int64_t)1 << 31)) return VENOM_ERR_UNSUPPORTED;  // gathered row ids are 32-bit
+  return VENOM_OK;
+}
+
+venom_status_t make_handle(int64_t R, int64_t K, int V, int N, int M, void* ws, size_t ws_bytes,
+                           venom_handle_t** out) {
+  const Layout L = venom::make_layout(R, K, V, M);
+  if (ws == nullptr || !aligned(ws, 256) || ws_bytes < L.total) return VENOM_ERR_WORKSPACE;
+  venom_handle_t* h = new (std::nothrow) venom_handle_t;
+  if (!h) return VENOM_ERR_INVALID_ARG;
+  h->R = R; h->K = K; h->V = V; h->N = N; h->M = M;
+  h->lay = L;
+  h->ws = static_cast<char*>(ws);
+  *out = h;
+  return VENOM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+venom_status_t venom_workspace_bytes(int64_t R, int64_t K, int V, int N, int M, size_t* bytes) {
+  if (!bytes) return VENOM_ERR_INVALID_ARG;
+  *bytes = 0;
+  venom_status_t s = check_shape(R, K, V, N, M);
+  if (s != VENOM_OK) return s;
+  *bytes = venom::make_layout(R, K, V, M).total;
+  return VENOM_OK;
+}
+
+venom_status_t venom_compress(const void* A_f16_dev, int64_t lda, const uint8_t* mask_dev, int64_t ldm, int64_t R,
+                              int64_t K, int V, int N, int M, void* workspace_dev, size_t workspace_bytes,
+                              void* stream, venom_handle_t** out, venom_violation_t* viol) {
+  if (!out) return VENOM_ERR_INVALID_ARG;
+  *out = nullptr;
+  if (viol) { viol->block_row = viol->group = viol->row = -1; }
+  venom_status_t s = check_shape(R, K, V, N, M);
+  if (s != VENOM_OK) return s;
+  if ((R > 0 && K > 0) && (!A_f16_dev || !mask_dev)) return VENOM_ERR_INVALID_ARG;
+  if (lda < K || ldm < K) return VENOM_ERR_SHAPE;
+  if (!aligned(A_f16_dev, 2)) return VENOM_ERR_UNSUPPORTED;
+  venom_handle_t* h = nullptr;
+  s = make_handle(R, K, V, N, M, workspace_dev, workspace_bytes, &h);
+  if (s != VENOM_OK) return s;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipError_t e = venom::launch_compress(static_cast<const uint16_t*>(A_f16_dev), lda, mask_dev, ldm, *h, st);
+  unsigned long long key = ~0ull;
+  if (e == hipSuccess)
+    e = hipMemcpyAsync(&key, h->ws + h->lay.off_status, sizeof(key), hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  if (e != hipSuccess) { delete h; return VENOM_ERR_HIP; }
+  if (key != ~0ull) {
+    const int64_t G = h->lay.G;
+    const int64_t blk = (int64_t)(key >> 24);
+    const bool row_rule = (key >> 23) & 1;
+    if (viol) {
+      viol->block_row = blk / G;
+      viol->group = blk % G;
+      viol->row = row_rule ? (blk / G) * V + (int64_t)(key & ((1u << 23) - 1)) : -1;
+    }
+    delete h;
+    return row_rule ? VENOM_ERR_MASK_ROW : VENOM_ERR_MASK_COLS;
+  }
+  e = venom::launch_pack(*h, st);
+  if (e != hipSuccess) { delete h; return VENOM_ERR_HIP; }
+  *out = h;
+  return VENOM_OK;
+}
+
+venom_status_t venom_import(const uint16_t* values_dev, const uint16_t* columns_dev, const uint32_t* meta_dev,
+                            int64_t R, int64_t K, int V, int N, int M, void* workspace_dev, size_t workspace_bytes,
+                            void* stream, venom_handle_t** out) {
+  if (!out) return VENOM_ERR_INVALID_ARG;
+  *out = nullptr;
+  venom_status_t s = check_shape(R, K, V, N, M);
+  if (s != VENOM_OK) return s;
+  if ((R > 0 && K > 0) && (!values_dev || !columns_dev || !meta_dev)) return VENOM_ERR_INVALID_ARG;
+  venom_handle_t* h = nullptr;
+  s = make_handle(R, K, V, N, M, workspace_dev, workspace_bytes, &h);
+  if (s != VENOM_OK) return s;
+  const Layout& L = h->lay;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipError_t e = hipSuccess;
+  if (R > 0 && K > 0) {
+    e = hipMemcpyAsync(h->ws + L.off_values, values_dev, (size_t)R * L.G * 4, hipMemcpyDeviceToDevice, st);
+    if (e == hipSuccess)
+      e = hipMemcpyAsync(h->ws + L.off_columns, columns_dev, (size_t)L.Rb * L.G * 8, hipMemcpyDeviceToDevice, st);
+    if (e == hipSuccess)
+      e = hipMemcpyAsync(h->ws + L.off_meta, meta_dev, (size_t)R * L.W * 4, hipMemcpyDeviceToDevice, st);
+    if (e == hipSuccess) e = venom::launch_pack(*h, st);
+  }
+  if (e != hipSuccess) { delete h; return VENOM_ERR_HIP; }
+  *out = h;
+  return VENOM_OK;
+}
+
+venom_status_t venom_export(const venom_handle_t* h, uint16_t* values_dev, uint16_t* columns_dev, uint32_t* meta_dev,
+                            void* stream) {
+  if (!h) return VENOM_ERR_INVALID_ARG;
+  const Layout& L = h->lay;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (h->R == 0 || h->K == 0) return VENOM_OK;
+  hipError_t e = hipSuccess;
+  if (values_dev)
+    e = hipMemcpyAsync(values_dev, h->ws + L.off_values, (size_t)h->R * L.G * 4, hipMemcpyDeviceToDevice, st);
+  if (e == hipSuccess && columns_dev)
+    e = hipMemcpyAsync(columns_dev, h->ws + L.off_columns, (size_t)L.Rb * L.G * 8, hipMemcpyDeviceToDevice, st);
+  if (e == hipSuccess && meta_dev)
+    e = hipMemcpyAsync(meta_dev, h->ws + L.off_meta, (size_t)h->R * L.W * 4, hipMemcpyDeviceToDevice, st);
+  return e == hipSuccess ? VENOM_OK : VENOM_ERR_HIP;
+}
+
+venom_status_t venom_decompress(const venom_handle_t* h, void* A_f16_dev, int64_t lda, void* stream) {
+  if (!h) return VENOM_ERR_INVALID_ARG;
+  if (h->R > 0 && h->K > 0 && !A_f16_dev) return VENOM_ERR_INVALID_ARG;
+  if (lda < h->K) return VENOM_ERR_SHAPE;
+  if (!h->lay.packed || !aligned(A_f16_dev, 2)) return VENOM_ERR_UNSUPPORTED;
+  hipError_t e = venom::launch_decompress(*h, static_cast<uint16_t*>(A_f16_dev), lda, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? VENOM_OK : VENOM_ERR_HIP;
+}
+
+venom_status_t venom_spmm_variant(const venom_handle_t* h, const void* B_f16_dev, int64_t ldb, int64_t C_cols,
+                                  void* C_dev, int64_t ldc, int c_dtype, int variant, void* stream) {
+  if (!h) return VENOM_ERR_INVALID_ARG;
+  if (c_dtype != 0 && c_dtype != 1) return VENOM_ERR_INVALID_ARG;
+  if (C_cols < 0) return VENOM_ERR_INVALID_ARG;
+  if (C_cols < 1) return VENOM_ERR_SHAPE;
+  if (ldb < C_cols || ldc < C_cols) return VENOM_ERR_SHAPE;
+  if ((h->K > 0 && !B_f16_dev) || (h->R > 0 && !C_dev)) return VENOM_ERR_INVALID_ARG;
+  if (h->V % venom::kTileRows != 0 || C_cols % 8 != 0) return VENOM_ERR_UNSUPPORTED;
+  const size_t esz = c_dtype == 1 ? 4 : 2;
+  if (!aligned(B_f16_dev, 16) || !aligned(C_dev, 16) || (ldb * 2) % 16 != 0 || (ldc * esz) % 16 != 0)
+    return VENOM_ERR_UNSUPPORTED;
+  return venom::launch_spmm(*h, B_f16_dev, ldb, C_cols, C_dev, ldc, c_dtype, variant, static_cast<hipStream_t>(stream));
+}
+
+venom_status_t venom_spmm(const venom_handle_t* h, const void* B_f16_dev, int64_t ldb, int64_t C_cols, void* C_dev,
+                          int64_t ldc, int c_dtype, void* stream) {
+  return venom_spmm_variant(h, B_f16_dev, ldb, C_cols, C_dev, ldc, c_dtype, -1, stream);
+}
+
+int venom_spmm_variant_count(void) { return venom::spmm_variant_count(); }
+const char* venom_spmm_variant_name(int variant) { return venom::spmm_variant_name(variant); }
+
+venom_status_t venom_get_info(const venom_handle_t* h, int64_t* R, int64_t* K, int* V, int* N, int* M) {
+  if (!h) return VENOM_ERR_INVALID_ARG;
+  if (R) *R = h->R;
+  if (K) *K = h->K;
+  if (V) *V = h->V;
+  if (N) *N = h->N;
+  if (M) *M = h->M;
+  return VENOM_OK;
+}
+
+void venom_destroy(venom_handle_t* h) { delete h; }
+
+const char* venom_status_string(venom_status_t s) {
+  switch (s) {
+    case VENOM_OK: return "ok";
+    case VENOM_ERR_INVALID_ARG: return "invalid argument";
+    case VENOM_ERR_SHAPE: return "shape not V:N:M-tileable or leading dimension too small";
+    case VENOM_ERR_UNSUPPORTED: return "unsupported configuration or alignment";
+    case VENOM_ERR_MASK_COLS: return "illegal mask: a V x M block uses more than 4 columns";
+    case VENOM_ERR_MASK_ROW: return "illegal mask: a row keeps more than 2 entries in a group of M";
+    case VENOM_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case VENOM_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,234 @@
+// Format kernels: dense + mask -> canonical V:N:M arrays (section 3 of the paper), canonical ->
+// the product kernel's packed copies, and packed -> dense (the format read backwards).
+// Pure data movement: fp16 payloads are handled as 16-bit patterns and never interpreted.
+#include "venom_internal.h"
+
+namespace venom {
+
+Layout make_layout(int64_t R, int64_t K, int V, int M) {
+  Layout L{};
+  L.R = R; L.K = K; L.G = K / M; L.Rb = R / V;
+  L.W = (L.G + 7) / 8;
+  L.steps = (L.G + kStepGroups - 1) / kStepGroups;
+  L.steps2 = (L.steps + 1) / 2;
+  L.packed = (V % kTileRows) == 0;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  L.off_values = take((size_t)R * L.G * 2 * sizeof(uint16_t));
+  L.off_columns = take((size_t)L.Rb * L.G * kSelCols * sizeof(uint16_t));
+  L.off_meta = take((size_t)R * L.W * sizeof(uint32_t));
+  if (L.packed) {
+    L.off_pvalues = take((size_t)(R / kTileRows) * L.steps * 64 * 16);
+    L.off_pmeta = take((size_t)(R / kTileRows) * L.steps2 * 64 * sizeof(uint32_t));
+    L.off_rowidx = take((size_t)L.Rb * L.steps * kStepRows * sizeof(int32_t));
+  }
+  L.off_status = take(8);
+  L.total = off;
+  return L;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Legality word: the smallest key wins, so the first offending block in row-major order is
+// reported, the column rule before the row rule inside one block, and the first row for the
+// row rule.  key = (block_linear << 24) | (kind << 23) | row_in_block.
+constexpr unsigned long long kNoViolation = ~0ull;
+
+__global__ void init_status_kernel(unsigned long long* status) { *status = kNoViolation; }
+
+// One workgroup per (block row b, metadata word w) = V rows x 8 groups x M columns.
+//   phase 1: which columns of each group are used by any row of the block (coalesced mask read)
+//   phase 2: eight threads pick the 4 columns of their group: the used ones ascending, padded with
+//            the smallest unused ids, sorted
+//   phase 3: one thread per row: positions kept inside the 4 selected columns, padded with the
+//            smallest unused positions, sorted -> nibble; values copied as bits
+constexpr int kMaxM = 1024;
+
+__global__ void __launch_bounds__(256) compress_kernel(const uint16_t* __restrict__ A, int64_t lda,
+                                                       const uint8_t* __restrict__ mask, int64_t ldm, int V, int M,
+                                                       int64_t G, int64_t W, uint32_t* __restrict__ values,
+                                                       uint16_t* __restrict__ columns, uint32_t* __restrict__ meta,
+                                                       unsigned long long* status) {
+  __shared__ uint8_t used[kStepGroups][kMaxM];
+  __shared__ int sel[kStepGroups][kSelCols];
+  __shared__ int cols_ok[kStepGroups];
+  const int64_t w = blockIdx.x, b = blockIdx.y;
+  const int tid = threadIdx.x;
+  const int64_t g0 = w * 8;
+  const int ng = (int)((G - g0) < 8 ? (G - g0) : 8);  // groups of this word that exist
+  const int span = ng * M;
+
+  for (int i = tid; i < kStepGroups * M; i += blockDim.x) used[i / M][i % M] = 0;
+  __syncthreads();
+  for (int64_t i = tid; i < (int64_t)V * span; i += blockDim.x) {
+    const int v = (int)(i / span), c = (int)(i % span);
+    if (mask[(b * V + v) * ldm + g0 * M + c]) used[c / M][c % M] = 1;  // benign: every writer stores 1
+  }
+  __syncthreads();
+  if (tid < ng) {
+    int cnt = 0, s[kSelCols];
+    for (int c = 0; c < M; ++c)
+      if (used[tid][c]) { if (cnt < kSelCols) s[cnt] = c; ++cnt; }
+    const bool ok = cnt <= kSelCols;
+    if (!ok) atomicMin(status, ((unsigned long long)(b * G + g0 + tid) << 24));
+    // pad with the smallest unused ids, keeping the list sorted
+    for (int c = 0; cnt < kSelCols && c < M; ++c) {
+      if (used[tid][c]) continue;
+      int pos = cnt;
+      while (pos > 0 && s[pos - 1] > c) { s[pos] = s[pos - 1]; --pos; }
+      s[pos] = c; ++cnt;
+    }
+    cols_ok[tid] = ok;
+    for (int p = 0; p < kSelCols; ++p) {
+      sel[tid][p] = s[p];
+      columns[((b * G) + g0 + tid) * kSelCols + p] = (uint16_t)s[p];
+    }
+  }
+  __syncthreads();
+  for (int v = tid; v < V; v += blockDim.x) {
+    const int64_t r = b * V + v;
+    uint32_t word = 0;
+    for (int t = 0; t < ng; ++t) {
+      const int64_t base = g0 + t;
+      const uint8_t* mrow = mask + r * ldm + base * M;
+      int kept[kSelCols], nk = 0;
+      for (int p = 0; p < kSelCols; ++p) { kept[p] = mrow[sel[t][p]] != 0; nk += kept[p]; }
+      if (cols_ok[t] && nk > 2)
+        atomicMin(status, ((unsigned long long)(b * G + base) << 24) | (1ull << 23) | (unsigned long long)v);
+      // first two kept positions, then the smallest unused ones, sorted
+      int p0 = -1, p1 = -1;
+      for (int p = 0; p < kSelCols; ++p)
+        if (kept[p]) { if (p0 < 0) p0 = p; else if (p1 < 0) p1 = p; }
+      bool k0 = p0 >= 0, k1 = p1 >= 0;
+      if (!k0) { p0 = 0; p1 = 1; }                     // nothing kept: positions (0, 1)
+      else if (!k1) {                                   // one kept: add the smallest other position
+        if (p0 == 0) { p1 = 1; }
+        else { p1 = p0; p0 = 0; k1 = true; k0 = false; }
+      }
+      const uint16_t* arow = A + r * lda + base * M;
+      const uint32_t v0 = k0 ? arow[sel[t][p0]] : 0u;
+      const uint32_t v1 = k1 ? arow[sel[t][p1]] : 0u;
+      values[r * G + base] = v0 | (v1 << 16);
+      word |= (uint32_t)(p0 | (p1 << 2)) << (4 * t);
+    }
+    meta[r * W + w] = word;
+  }
+}
+
+// canonical -> packed, one thread per 16-byte (resp. 4-byte) element of the packed arrays.
+// Packed values: [R/32][steps][64 lanes][8 halfs]; lane = 32*h + i holds row 32*tile + i and the
+// groups 8*step + 4*h .. +3 (two values each) -- the A operand of v_smfmac_f32_32x32x32_f16.
+__global__ void __launch_bounds__(256) pack_values_kernel(const uint32_t* __restrict__ values, int64_t G,
+                                                          int64_t steps, int64_t total, uint4* __restrict__ pvalues) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int lane = (int)(idx % 64);
+  const int64_t s = (idx / 64) % steps, rt = idx / 64 / steps;
+  const int64_t r = rt * kTileRows + (lane % 32);
+  const int64_t g = s * 8 + 4 * (lane / 32);
+  uint32_t v[4];
+  for (int e = 0; e < 4; ++e) v[e] = (g + e < G) ? values[r * G + g + e] : 0u;
+  pvalues[idx] = make_uint4(v[0], v[1], v[2], v[3]);
+}
+
+// Packed metadata: [R/32][steps2][64 lanes] words; the low half holds the lane's four nibbles of
+// k-step 2*s2, the high half those of k-step 2*s2 + 1 (the instruction's ABID picks the half).
+__global__ void __launch_bounds__(256) pack_meta_kernel(const uint32_t* __restrict__ meta, int64_t W, int64_t steps2,
+                                                        int64_t total, uint32_t* __restrict__ pmeta) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int lane = (int)(idx % 64);
+  const int64_t s2 = (idx / 64) % steps2, rt = idx / 64 / steps2;
+  const int64_t r = rt * kTileRows + (lane % 32);
+  const int sh = 16 * (lane / 32);
+  const uint32_t lo = (2 * s2 < W) ? (meta[r * W + 2 * s2] >> sh) & 0xffffu : 0u;
+  const uint32_t hi = (2 * s2 + 1 < W) ? (meta[r * W + 2 * s2 + 1] >> sh) & 0xffffu : 0u;
+  pmeta[idx] = lo | (hi << 16);
+}
+
+// Absolute row of B for every gathered row: [R/V][steps][32], entry 4*t + p of a step is
+// (8*step + t)*M + column_loc[p]; groups past the end point at row 0 (their values are zero).
+__global__ void __launch_bounds__(256) pack_rowidx_kernel(const uint16_t* __restrict__ columns, int64_t G, int M,
+                                                          int64_t steps, int64_t total, int32_t* __restrict__ rowidx) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int rho = (int)(idx % kStepRows);
+  const int64_t s = (idx / kStepRows) % steps, b = idx / kStepRows / steps;
+  const int64_t g = s * 8 + rho / 4;
+  rowidx[idx] = (g < G) ? (int32_t)(g * M + columns[(b * G + g) * kSelCols + (rho % 4)]) : 0;
+}
+
+// packed -> dense: one thread per output element.
+__global__ void __launch_bounds__(256) decompress_kernel(const uint16_t* __restrict__ pvalues,
+                                                         const uint32_t* __restrict__ pmeta,
+                                                         const int32_t* __restrict__ rowidx, int64_t R, int64_t K, int V,
+                                                         int M, int64_t steps, int64_t steps2, uint16_t* __restrict__ A,
+                                                         int64_t lda) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= R * K) return;
+  const int64_t r = idx / K, k = idx % K;
+  const int64_t g = k / M, s = g / 8;
+  const int t = (int)(g % 8), h = t / 4, ge = t % 4;
+  const int64_t rt = r / kTileRows;
+  const int lane = 32 * h + (int)(r % kTileRows);
+  const uint32_t word = pmeta[(rt * steps2 + s / 2) * 64 + lane];
+  const uint32_t nib = (word >> (16 * (s % 2) + 4 * ge)) & 0xfu;
+  const int32_t* ri = rowidx + ((r / V) * steps + s) * kStepRows + 4 * t;
+  const uint16_t* pv = pvalues + ((rt * steps + s) * 64 + lane) * 8 + 2 * ge;
+  uint16_t out = 0;
+  if (ri[nib & 3] == k) out = pv[0];
+  if (ri[nib >> 2] == k) out = pv[1];
+  A[r * lda + k] = out;
+}
+
+static inline unsigned blocks_for(int64_t total) { return (unsigned)((total + 255) / 256); }
+
+hipError_t launch_compress(const uint16_t* A, int64_t lda, const uint8_t* mask, int64_t ldm, const venom_handle& h,
+                           hipStream_t st) {
+  const Layout& L = h.lay;
+  auto* status = reinterpret_cast<unsigned long long*>(h.ws + L.off_status);
+  hipLaunchKernelGGL(init_status_kernel, dim3(1), dim3(1), 0, st, status);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (L.R > 0 && L.G > 0) {
+    dim3 grid((unsigned)L.W, (unsigned)L.Rb);
+    hipLaunchKernelGGL(compress_kernel, grid, dim3(256), 0, st, A, lda, mask, ldm, h.V, h.M, L.G, L.W,
+                       reinterpret_cast<uint32_t*>(h.ws + L.off_values),
+                       reinterpret_cast<uint16_t*>(h.ws + L.off_columns),
+                       reinterpret_cast<uint32_t*>(h.ws + L.off_meta), status);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+hipError_t launch_pack(const venom_handle& h, hipStream_t st) {
+  const Layout& L = h.lay;
+  if (!L.packed || L.R == 0 || L.G == 0) return hipSuccess;
+  const int64_t tiles = L.R / kTileRows;
+  int64_t total = tiles * L.steps * 64;
+  hipLaunchKernelGGL(pack_values_kernel, dim3(blocks_for(total)), dim3(256), 0, st,
+                     reinterpret_cast<const uint32_t*>(h.ws + L.off_values), L.G, L.steps, total,
+                     reinterpret_cast<uint4*>(h.ws + L.off_pvalues));
+  total = tiles * L.steps2 * 64;
+  hipLaunchKernelGGL(pack_meta_kernel, dim3(blocks_for(total)), dim3(256), 0, st,
+                     reinterpret_cast<const uint32_t*>(h.ws + L.off_meta), L.W, L.steps2, total,
+                     reinterpret_cast<uint32_t*>(h.ws + L.off_pmeta));
+  total = L.Rb * L.steps * kStepRows;
+  hipLaunchKernelGGL(pack_rowidx_kernel, dim3(blocks_for(total)), dim3(256), 0, st,
+                     reinterpret_cast<const uint16_t*>(h.ws + L.off_columns), L.G, h.M, L.steps, total,
+                     reinterpret_cast<int32_t*>(h.ws + L.off_rowidx));
+  return hipGetLastError();
+}
+
+hipError_t launch_decompress(const venom_handle& h, uint16_t* A, int64_t lda, hipStream_t st) {
+  const Layout& L = h.lay;
+  if (L.R == 0 || L.K == 0) return hipSuccess;
+  const int64_t total = L.R * L.K;
+  hipLaunchKernelGGL(decompress_kernel, dim3(blocks_for(total)), dim3(256), 0, st,
+                     reinterpret_cast<const uint16_t*>(h.ws + L.off_pvalues),
+                     reinterpret_cast<const uint32_t*>(h.ws + L.off_pmeta),
+                     reinterpret_cast<const int32_t*>(h.ws + L.off_rowidx), L.R, L.K, h.V, h.M, L.steps, L.steps2, A,
+                     lda);
+  return hipGetLastError();
+}
+
+}  // namespace venom

@@ -1,0 +1,57 @@
+// Internal declarations shared by the library's translation units (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "venom.h"
+
+namespace venom {
+
+constexpr int kSelCols = 4;    // columns kept per V x M block (section 3)
+constexpr int kTileRows = 32;  // rows of one matrix-instruction tile (v_smfmac_f32_32x32x32_f16)
+constexpr int kStepGroups = 8; // groups of M columns consumed per k-step: 8 groups x 4 columns = 32
+constexpr int kStepRows = kStepGroups * kSelCols;  // gathered rows of B per k-step
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Where each array lives inside the caller's workspace (byte offsets, all 256-byte aligned).
+struct Layout {
+  int64_t R, K, G, Rb, W;  // G = K/M groups per row, Rb = R/V block rows, W = ceil(G/8) meta words per row
+  int64_t steps;           // k-steps = ceil(G/8)
+  int64_t steps2;          // pairs of k-steps = ceil(steps/2)
+  bool packed;             // V % 32 == 0: the kernel's packed copies exist
+  size_t off_values, off_columns, off_meta;      // canonical
+  size_t off_pvalues, off_pmeta, off_rowidx;     // packed for the kernel
+  size_t off_status;                             // 8-byte legality word
+  size_t total;
+};
+
+Layout make_layout(int64_t R, int64_t K, int V, int M);
+
+}  // namespace venom
+
+struct venom_handle {
+  int64_t R, K;
+  int V, N, M;
+  venom::Layout lay;
+  char* ws;  // borrowed device pointer
+};
+
+namespace venom {
+
+// ---- format kernels (venom_format.hip)
+hipError_t launch_compress(const uint16_t* A, int64_t lda, const uint8_t* mask, int64_t ldm, const venom_handle& h,
+                           hipStream_t st);
+hipError_t launch_pack(const venom_handle& h, hipStream_t st);
+hipError_t launch_decompress(const venom_handle& h, uint16_t* A, int64_t lda, hipStream_t st);
+
+// ---- product kernels (venom_spmm.hip)
+int spmm_variant_count();
+const char* spmm_variant_name(int v);
+// returns VENOM_OK / VENOM_ERR_UNSUPPORTED / VENOM_ERR_HIP
+venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, int64_t Ccols, void* C, int64_t ldc,
+                           int c_dtype, int variant, hipStream_t st);
+
+}  // namespace venom

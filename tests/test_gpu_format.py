@@ -1,0 +1,167 @@
+"""GPU parity of the format path (venom_compress / export / import / decompress) against the CPU
+oracle: bit-exact on every array, on the same seeded inputs."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import vnm_oracle as o
+from paper_2310_02065_amd import binding, inputs
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def to_dev_f16(bits):
+    return torch.from_numpy(bits.view(np.float16)).to(DEV)
+
+
+def export_np(h):
+    v, c, m = binding.venom_export(h)
+    torch.cuda.synchronize()
+    return (v.cpu().numpy().view(np.uint16), c.cpu().numpy().view(np.uint16), m.cpu().numpy().view(np.uint32))
+
+
+def check_compress(A, mask, V, M):
+    h = binding.venom_compress(to_dev_f16(A), torch.from_numpy(mask).to(DEV), V, 2, M)
+    v, c, m = export_np(h)
+    ov, oc, om = o.compress(A, mask, V, M)
+    assert np.array_equal(c, oc), "column-loc differs"
+    assert np.array_equal(m, om), "metadata differs"
+    assert np.array_equal(v, ov), "values differ"
+    return h
+
+
+SHAPES = [
+    (256, 256, 64, 8),       # the tiny config
+    (128, 320, 32, 10),      # M not a power of two
+    (256, 1024, 128, 32),
+    (64, 1400, 64, 100),     # 2:100, G = 14 (ragged last metadata word)
+    (96, 84, 32, 7),         # 2:7, G = 12
+    (128, 64, 64, 4),        # plain 2:4
+    (40, 48, 8, 6),          # V not a multiple of 32: format only
+    (3072, 768, 64, 8),      # BERT-base FFN-up
+]
+
+
+@pytest.mark.parametrize("R,K,V,M", SHAPES)
+def test_compress_bit_exact_and_decompress(R, K, V, M):
+    A, mask, _ = inputs.gen_problem(R, K, 8, V, M, 1.0, seed=31 + M + R)
+    h = check_compress(A, mask, V, M)
+    assert binding.venom_get_info(h) == (R, K, V, 2, M)
+    if V % 32 == 0:
+        d = binding.venom_decompress(h)
+        torch.cuda.synchronize()
+        assert np.array_equal(d.cpu().numpy().view(np.uint16), np.where(mask != 0, A, 0))
+    else:
+        with pytest.raises(binding.VenomError) as e:
+            binding.venom_decompress(h)
+        assert e.value.status == binding.VENOM_ERR_UNSUPPORTED
+
+
+def test_hand_fixture_on_gpu():
+    from helpers import load_hand_fixture
+    fx = load_hand_fixture()
+    h = binding.venom_compress(to_dev_f16(fx["A_bits"]), torch.from_numpy(fx["mask"]).to(DEV), fx["V"], 2, fx["M"])
+    v, c, m = export_np(h)
+    assert np.array_equal(v, fx["values"]) and np.array_equal(c, fx["columns"]) and np.array_equal(m, fx["meta"])
+
+
+def test_padding_and_special_values():
+    # sparse-in-structure mask: blocks with 0..3 used columns, rows with 0 or 1 kept entries;
+    # payloads include -0, inf, NaN patterns and subnormals, copied as bits
+    R, K, V, M = 64, 128, 32, 16
+    rng = np.random.default_rng(5)
+    A = rng.integers(0, 1 << 16, size=(R, K), dtype=np.uint16)
+    full = inputs.gen_mask(R, K, V, M, rng)
+    drop = rng.random((R, K)) < 0.6
+    mask = np.where(drop, 0, full).astype(np.uint8)
+    mask[0:32, 0:16] = 0                      # an entirely empty block
+    h = check_compress(A, mask, V, M)
+    d = binding.venom_decompress(h)
+    torch.cuda.synchronize()
+    assert np.array_equal(d.cpu().numpy().view(np.uint16), np.where(mask != 0, A, 0))
+
+
+def test_strided_inputs():
+    R, K, V, M = 128, 256, 64, 8
+    A, mask, _ = inputs.gen_problem(R, K, 8, V, M, 1.0, seed=77)
+    Abig = torch.zeros((R, K + 24), dtype=torch.float16, device=DEV)
+    Mbig = torch.ones((R, K + 40), dtype=torch.uint8, device=DEV)
+    Abig[:, :K] = to_dev_f16(A)
+    Mbig[:, :K] = torch.from_numpy(mask).to(DEV)
+    h = binding.venom_compress(Abig[:, :K], Mbig[:, :K], V, 2, M)
+    v, c, m = export_np(h)
+    ov, oc, om = o.compress(A, mask, V, M)
+    assert np.array_equal(v, ov) and np.array_equal(c, oc) and np.array_equal(m, om)
+
+
+def test_illegal_masks_report_first_offender():
+    R, K, V, M = 128, 256, 64, 8
+    A, mask, _ = inputs.gen_problem(R, K, 8, V, M, 1.0, seed=13)
+    Ad = to_dev_f16(A)
+
+    def run(bad):
+        status, where = o.check_mask(bad, V, M)
+        with pytest.raises(binding.VenomError) as e:
+            binding.venom_compress(Ad, torch.from_numpy(bad).to(DEV), V, 2, M)
+        want = binding.VENOM_ERR_MASK_COLS if status == o.ERR_MASK_COLS else binding.VENOM_ERR_MASK_ROW
+        assert e.value.status == want and tuple(e.value.violation) == tuple(where)
+
+    # fifth column in block (1, 5)
+    bad = mask.copy()
+    blk = bad[64:128, 40:48]
+    free, old = int(np.flatnonzero(~blk.any(axis=0))[0]), int(np.flatnonzero(blk[3])[0])
+    blk[3, old] = 0
+    blk[3, free] = 1
+    assert o.check_mask(bad, V, M) == (o.ERR_MASK_COLS, (1, 5, -1))
+    run(bad)
+    # third entry in a row of block (0, 7), plus a later column violation: the earlier block wins
+    bad2 = bad.copy()
+    blk0 = bad2[0:64, 56:64]
+    used = np.flatnonzero(blk0.any(axis=0))
+    blk0[17, [c for c in used if not blk0[17, c]][0]] = 1
+    assert o.check_mask(bad2, V, M)[0] == o.ERR_MASK_ROW
+    run(bad2)
+    # two offending rows in one block: the first row is named
+    blk0[9, [c for c in used if not blk0[9, c]][0]] = 1
+    run(bad2)
+    # both rules in one block: the column rule is reported
+    bad3 = mask.copy()
+    b3 = bad3[0:64, 0:8]
+    b3[5, :] = 1
+    assert o.check_mask(bad3, V, M)[0] == o.ERR_MASK_COLS
+    run(bad3)
+
+
+def test_import_roundtrip():
+    R, K, V, M = 128, 512, 64, 16
+    A, mask, _ = inputs.gen_problem(R, K, 8, V, M, 1.0, seed=21)
+    ov, oc, om = o.compress(A, mask, V, M)
+    dv = torch.from_numpy(ov.view(np.int16)).to(DEV)
+    dc = torch.from_numpy(oc.view(np.int16)).to(DEV)
+    dm = torch.from_numpy(om.view(np.int32)).to(DEV)
+    h = binding.venom_import(dv, dc, dm, R, K, V, 2, M)
+    v, c, m = export_np(h)
+    assert np.array_equal(v, ov) and np.array_equal(c, oc) and np.array_equal(m, om)
+    d = binding.venom_decompress(h)
+    torch.cuda.synchronize()
+    assert np.array_equal(d.cpu().numpy().view(np.uint16), o.decompress(ov, oc, om, R, K, V, M))
+
+
+def test_workspace_errors():
+    L = binding.lib()
+    import ctypes
+    R, K, V, M = 64, 64, 32, 8
+    A = torch.zeros((R, K), dtype=torch.float16, device=DEV)
+    mask = torch.zeros((R, K), dtype=torch.uint8, device=DEV)
+    need = binding.venom_workspace_bytes(R, K, V, 2, M)
+    ws = torch.empty(need + 512, dtype=torch.uint8, device=DEV)
+    base = ws.data_ptr() + ((-ws.data_ptr()) % 256)
+    out = ctypes.c_void_p(0)
+    args = lambda p, n: (ctypes.c_void_p(A.data_ptr()), K, ctypes.c_void_p(mask.data_ptr()), K, R, K, V, 2, M,
+                         ctypes.c_void_p(p), n, None, ctypes.byref(out), None)
+    assert L.venom_compress(*args(base, need - 1)) == binding.VENOM_ERR_WORKSPACE
+    assert L.venom_compress(*args(base + 8, need)) == binding.VENOM_ERR_WORKSPACE
+    assert L.venom_compress(*args(base, need)) == binding.VENOM_OK and out.value
+    L.venom_destroy(out)
