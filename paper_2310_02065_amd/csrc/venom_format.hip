@@ -10,17 +10,17 @@ Layout make_layout(int64_t R, int64_t K, int V, int M) {
   L.R = R; L.K = K; L.G = K / M; L.Rb = R / V;
   L.W = (L.G + 7) / 8;
   L.steps = (L.G + kStepGroups - 1) / kStepGroups;
-  L.steps2 = (L.steps + 1) / 2;
   L.packed = (V % kTileRows) == 0;
+  L.vt = L.packed ? V / kTileRows : 0;
+  L.rec_bytes = (int64_t)L.vt * (kTileValBytes + kTileIdxBytes);
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   L.off_values = take((size_t)R * L.G * 2 * sizeof(uint16_t));
   L.off_columns = take((size_t)L.Rb * L.G * kSelCols * sizeof(uint16_t));
   L.off_meta = take((size_t)R * L.W * sizeof(uint32_t));
   if (L.packed) {
-    L.off_pvalues = take((size_t)(R / kTileRows) * L.steps * 64 * 16);
-    L.off_pmeta = take((size_t)(R / kTileRows) * L.steps2 * 64 * sizeof(uint32_t));
-    L.off_rowidx = take((size_t)L.Rb * L.steps * kStepRows * sizeof(int32_t));
+    L.off_arec = take((size_t)L.Rb * L.steps * L.rec_bytes);
+    L.off_rowidx = take(((size_t)L.Rb * L.steps * kStepRows + kRowIdxSlack) * sizeof(int32_t));
   }
   L.off_status = take(8);
   L.total = off;
@@ -114,43 +114,41 @@ __global__ void __launch_bounds__(256) compress_kernel(const uint16_t* __restric
   }
 }
 
-// canonical -> packed, one thread per 16-byte (resp. 4-byte) element of the packed arrays.
-// Packed values: [R/32][steps][64 lanes][8 halfs]; lane = 32*h + i holds row 32*tile + i and the
-// groups 8*step + 4*h .. +3 (two values each) -- the A operand of v_smfmac_f32_32x32x32_f16.
-__global__ void __launch_bounds__(256) pack_values_kernel(const uint32_t* __restrict__ values, int64_t G,
-                                                          int64_t steps, int64_t total, uint4* __restrict__ pvalues) {
+// canonical -> the kernel's packed A stream.  One record per (block row, k-step):
+//   [V/32 tiles x 1024 B of values][V/32 tiles x 256 B of index words]
+// values of a tile: 64 lanes x 8 halfs; lane = 32*h + i holds row 32*tile + i and the two kept
+// values of groups 8*step + 4*h .. +3 -- the A operand of v_smfmac_f32_32x32x32_f16.
+// index words of a tile: 64 lanes x uint32; the low 16 bits are the lane's four canonical nibbles
+// (the matrix instruction reads them with ABID = 0), the high 16 bits are zero.
+// One thread per lane-slot of the values (16 B) and of the index words (4 B).
+__global__ void __launch_bounds__(256) pack_arec_kernel(const uint32_t* __restrict__ values,
+                                                        const uint32_t* __restrict__ meta, int64_t G, int64_t W,
+                                                        int64_t steps, int vt, int V, int64_t total,
+                                                        char* __restrict__ arec) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= total) return;
   const int lane = (int)(idx % 64);
-  const int64_t s = (idx / 64) % steps, rt = idx / 64 / steps;
-  const int64_t r = rt * kTileRows + (lane % 32);
-  const int64_t g = s * 8 + 4 * (lane / 32);
+  const int tile = (int)((idx / 64) % vt);
+  const int64_t s = (idx / 64 / vt) % steps, b = idx / 64 / vt / steps;
+  const int64_t r = b * V + tile * kTileRows + (lane % 32);
+  const int h = lane / 32;
+  const int64_t g = s * 8 + 4 * h;
   uint32_t v[4];
   for (int e = 0; e < 4; ++e) v[e] = (g + e < G) ? values[r * G + g + e] : 0u;
-  pvalues[idx] = make_uint4(v[0], v[1], v[2], v[3]);
+  char* rec = arec + (b * steps + s) * (int64_t)vt * (kTileValBytes + kTileIdxBytes);
+  reinterpret_cast<uint4*>(rec + tile * kTileValBytes)[lane] = make_uint4(v[0], v[1], v[2], v[3]);
+  const uint32_t word = (s < W) ? (meta[r * W + s] >> (16 * h)) & 0xffffu : 0u;
+  reinterpret_cast<uint32_t*>(rec + vt * kTileValBytes + tile * kTileIdxBytes)[lane] = word;
 }
 
-// Packed metadata: [R/32][steps2][64 lanes] words; the low half holds the lane's four nibbles of
-// k-step 2*s2, the high half those of k-step 2*s2 + 1 (the instruction's ABID picks the half).
-__global__ void __launch_bounds__(256) pack_meta_kernel(const uint32_t* __restrict__ meta, int64_t W, int64_t steps2,
-                                                        int64_t total, uint32_t* __restrict__ pmeta) {
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= total) return;
-  const int lane = (int)(idx % 64);
-  const int64_t s2 = (idx / 64) % steps2, rt = idx / 64 / steps2;
-  const int64_t r = rt * kTileRows + (lane % 32);
-  const int sh = 16 * (lane / 32);
-  const uint32_t lo = (2 * s2 < W) ? (meta[r * W + 2 * s2] >> sh) & 0xffffu : 0u;
-  const uint32_t hi = (2 * s2 + 1 < W) ? (meta[r * W + 2 * s2 + 1] >> sh) & 0xffffu : 0u;
-  pmeta[idx] = lo | (hi << 16);
-}
-
-// Absolute row of B for every gathered row: [R/V][steps][32], entry 4*t + p of a step is
-// (8*step + t)*M + column_loc[p]; groups past the end point at row 0 (their values are zero).
+// Absolute row of B for every gathered row: [R/V][steps][32] (+ readable slack), entry 4*t + p of a
+// step is (8*step + t)*M + column_loc[p]; groups past the end point at row 0 (their values are zero).
 __global__ void __launch_bounds__(256) pack_rowidx_kernel(const uint16_t* __restrict__ columns, int64_t G, int M,
-                                                          int64_t steps, int64_t total, int32_t* __restrict__ rowidx) {
+                                                          int64_t steps, int64_t total, int64_t total_padded,
+                                                          int32_t* __restrict__ rowidx) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= total) return;
+  if (idx >= total_padded) return;
+  if (idx >= total) { rowidx[idx] = 0; return; }
   const int rho = (int)(idx % kStepRows);
   const int64_t s = (idx / kStepRows) % steps, b = idx / kStepRows / steps;
   const int64_t g = s * 8 + rho / 4;
@@ -158,22 +156,22 @@ __global__ void __launch_bounds__(256) pack_rowidx_kernel(const uint16_t* __rest
 }
 
 // packed -> dense: one thread per output element.
-__global__ void __launch_bounds__(256) decompress_kernel(const uint16_t* __restrict__ pvalues,
-                                                         const uint32_t* __restrict__ pmeta,
+__global__ void __launch_bounds__(256) decompress_kernel(const char* __restrict__ arec,
                                                          const int32_t* __restrict__ rowidx, int64_t R, int64_t K, int V,
-                                                         int M, int64_t steps, int64_t steps2, uint16_t* __restrict__ A,
+                                                         int M, int64_t steps, int vt, uint16_t* __restrict__ A,
                                                          int64_t lda) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= R * K) return;
   const int64_t r = idx / K, k = idx % K;
-  const int64_t g = k / M, s = g / 8;
+  const int64_t g = k / M, s = g / 8, b = r / V;
   const int t = (int)(g % 8), h = t / 4, ge = t % 4;
-  const int64_t rt = r / kTileRows;
+  const int tile = (int)((r % V) / kTileRows);
   const int lane = 32 * h + (int)(r % kTileRows);
-  const uint32_t word = pmeta[(rt * steps2 + s / 2) * 64 + lane];
-  const uint32_t nib = (word >> (16 * (s % 2) + 4 * ge)) & 0xfu;
-  const int32_t* ri = rowidx + ((r / V) * steps + s) * kStepRows + 4 * t;
-  const uint16_t* pv = pvalues + ((rt * steps + s) * 64 + lane) * 8 + 2 * ge;
+  const char* rec = arec + (b * steps + s) * (int64_t)vt * (kTileValBytes + kTileIdxBytes);
+  const uint32_t word = reinterpret_cast<const uint32_t*>(rec + vt * kTileValBytes + tile * kTileIdxBytes)[lane];
+  const uint32_t nib = (word >> (4 * ge)) & 0xfu;
+  const int32_t* ri = rowidx + (b * steps + s) * kStepRows + 4 * t;
+  const uint16_t* pv = reinterpret_cast<const uint16_t*>(rec + tile * kTileValBytes) + lane * 8 + 2 * ge;
   uint16_t out = 0;
   if (ri[nib & 3] == k) out = pv[0];
   if (ri[nib >> 2] == k) out = pv[1];
@@ -203,19 +201,15 @@ hipError_t launch_compress(const uint16_t* A, int64_t lda, const uint8_t* mask, 
 hipError_t launch_pack(const venom_handle& h, hipStream_t st) {
   const Layout& L = h.lay;
   if (!L.packed || L.R == 0 || L.G == 0) return hipSuccess;
-  const int64_t tiles = L.R / kTileRows;
-  int64_t total = tiles * L.steps * 64;
-  hipLaunchKernelGGL(pack_values_kernel, dim3(blocks_for(total)), dim3(256), 0, st,
-                     reinterpret_cast<const uint32_t*>(h.ws + L.off_values), L.G, L.steps, total,
-                     reinterpret_cast<uint4*>(h.ws + L.off_pvalues));
-  total = tiles * L.steps2 * 64;
-  hipLaunchKernelGGL(pack_meta_kernel, dim3(blocks_for(total)), dim3(256), 0, st,
-                     reinterpret_cast<const uint32_t*>(h.ws + L.off_meta), L.W, L.steps2, total,
-                     reinterpret_cast<uint32_t*>(h.ws + L.off_pmeta));
+  int64_t total = L.Rb * L.steps * L.vt * 64;
+  hipLaunchKernelGGL(pack_arec_kernel, dim3(blocks_for(total)), dim3(256), 0, st,
+                     reinterpret_cast<const uint32_t*>(h.ws + L.off_values),
+                     reinterpret_cast<const uint32_t*>(h.ws + L.off_meta), L.G, L.W, L.steps, L.vt, h.V, total,
+                     h.ws + L.off_arec);
   total = L.Rb * L.steps * kStepRows;
-  hipLaunchKernelGGL(pack_rowidx_kernel, dim3(blocks_for(total)), dim3(256), 0, st,
+  hipLaunchKernelGGL(pack_rowidx_kernel, dim3(blocks_for(total + kRowIdxSlack)), dim3(256), 0, st,
                      reinterpret_cast<const uint16_t*>(h.ws + L.off_columns), L.G, h.M, L.steps, total,
-                     reinterpret_cast<int32_t*>(h.ws + L.off_rowidx));
+                     total + kRowIdxSlack, reinterpret_cast<int32_t*>(h.ws + L.off_rowidx));
   return hipGetLastError();
 }
 
@@ -223,11 +217,8 @@ hipError_t launch_decompress(const venom_handle& h, uint16_t* A, int64_t lda, hi
   const Layout& L = h.lay;
   if (L.R == 0 || L.K == 0) return hipSuccess;
   const int64_t total = L.R * L.K;
-  hipLaunchKernelGGL(decompress_kernel, dim3(blocks_for(total)), dim3(256), 0, st,
-                     reinterpret_cast<const uint16_t*>(h.ws + L.off_pvalues),
-                     reinterpret_cast<const uint32_t*>(h.ws + L.off_pmeta),
-                     reinterpret_cast<const int32_t*>(h.ws + L.off_rowidx), L.R, L.K, h.V, h.M, L.steps, L.steps2, A,
-                     lda);
+  hipLaunchKernelGGL(decompress_kernel, dim3(blocks_for(total)), dim3(256), 0, st, h.ws + L.off_arec,
+                     reinterpret_cast<const int32_t*>(h.ws + L.off_rowidx), L.R, L.K, h.V, h.M, L.steps, L.vt, A, lda);
   return hipGetLastError();
 }
 

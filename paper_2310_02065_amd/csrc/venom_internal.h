@@ -13,6 +13,9 @@ constexpr int kSelCols = 4;    // columns kept per V x M block (section 3)
 constexpr int kTileRows = 32;  // rows of one matrix-instruction tile (v_smfmac_f32_32x32x32_f16)
 constexpr int kStepGroups = 8; // groups of M columns consumed per k-step: 8 groups x 4 columns = 32
 constexpr int kStepRows = kStepGroups * kSelCols;  // gathered rows of B per k-step
+constexpr int kTileValBytes = 1024;                // packed values of one 32-row tile for one k-step
+constexpr int kTileIdxBytes = 256;                 // packed index words of one 32-row tile for one k-step
+constexpr int kRowIdxSlack = 256;                  // readable int32 entries past the end of the row-id array
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -20,10 +23,11 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 struct Layout {
   int64_t R, K, G, Rb, W;  // G = K/M groups per row, Rb = R/V block rows, W = ceil(G/8) meta words per row
   int64_t steps;           // k-steps = ceil(G/8)
-  int64_t steps2;          // pairs of k-steps = ceil(steps/2)
+  int vt;                  // 32-row tiles per block row (V/32) when packed
+  int64_t rec_bytes;       // bytes of one (block row, k-step) record of the packed A stream
   bool packed;             // V % 32 == 0: the kernel's packed copies exist
   size_t off_values, off_columns, off_meta;      // canonical
-  size_t off_pvalues, off_pmeta, off_rowidx;     // packed for the kernel
+  size_t off_arec, off_rowidx;                   // packed for the kernel
   size_t off_status;                             // 8-byte legality word
   size_t total;
 };
