@@ -10,9 +10,9 @@ Layout make_layout(int64_t R, int64_t K, int V, int M) {
   L.R = R; L.K = K; L.G = K / M; L.Rb = R / V;
   L.W = (L.G + 7) / 8;
   L.steps = (L.G + kStepGroups - 1) / kStepGroups;
-  L.packed = (V % kTileRows) == 0;
+  L.packed = (V % kTileRows) == 0 && V / kTileRows <= kMaxTiles;
   L.vt = L.packed ? V / kTileRows : 0;
-  L.rec_bytes = (int64_t)L.vt * (kTileValBytes + kTileIdxBytes);
+  L.rec_bytes = (int64_t)L.vt * kTileValBytes + kTailBytes;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   L.off_values = take((size_t)R * L.G * 2 * sizeof(uint16_t));
@@ -20,7 +20,7 @@ Layout make_layout(int64_t R, int64_t K, int V, int M) {
   L.off_meta = take((size_t)R * L.W * sizeof(uint32_t));
   if (L.packed) {
     L.off_arec = take((size_t)L.Rb * L.steps * L.rec_bytes);
-    L.off_rowidx = take(((size_t)L.Rb * L.steps * kStepRows + kRowIdxSlack) * sizeof(int32_t));
+    L.off_rowidx = take((size_t)L.Rb * L.steps * kStepRows * sizeof(int32_t));
   }
   L.off_status = take(8);
   L.total = off;
@@ -114,45 +114,61 @@ __global__ void __launch_bounds__(256) compress_kernel(const uint16_t* __restric
   }
 }
 
+// Absolute row of B for every gathered row: [R/V][steps][32], entry 4*t + p of a step is
+// (8*step + t)*M + column_loc[p]; groups past the end point at row 0 (their values are zero).
+__global__ void __launch_bounds__(256) pack_rowidx_kernel(const uint16_t* __restrict__ columns, int64_t G, int M,
+                                                          int64_t steps, int64_t total, int32_t* __restrict__ rowidx) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int rho = (int)(idx % kStepRows);
+  const int64_t s = (idx / kStepRows) % steps, b = idx / kStepRows / steps;
+  const int64_t g = s * 8 + rho / 4;
+  rowidx[idx] = (g < G) ? (int32_t)(g * M + columns[(b * G + g) * kSelCols + (rho % 4)]) : 0;
+}
+
 // canonical -> the kernel's packed A stream.  One record per (block row, k-step):
-//   [V/32 tiles x 1024 B of values][V/32 tiles x 256 B of index words]
+//   [V/32 tiles x 1024 B of values][1024 B tail]
 // values of a tile: 64 lanes x 8 halfs; lane = 32*h + i holds row 32*tile + i and the two kept
 // values of groups 8*step + 4*h .. +3 -- the A operand of v_smfmac_f32_32x32x32_f16.
-// index words of a tile: 64 lanes x uint32; the low 16 bits are the lane's four canonical nibbles
-// (the matrix instruction reads them with ABID = 0), the high 16 bits are zero.
-// One thread per lane-slot of the values (16 B) and of the index words (4 B).
+// tail: bytes [0, 512): 64 lanes x 4 x uint16, entry [lane][tile] = the lane's four canonical nibbles
+//       for that tile (a lane reads its 8 bytes with one LDS load; the matrix instruction picks
+//       the 16-bit field with its ABID operand); bytes [512, 640): the 32 B-row ids of k-step
+//       step + kRidLead (0 past the end), so the gather addresses travel with the stream;
+//       the rest is zero.
+// One thread per lane-slot: (block row, step, tile, lane) for tile < vt; tile == vt writes the
+// row ids and the padding.
 __global__ void __launch_bounds__(256) pack_arec_kernel(const uint32_t* __restrict__ values,
-                                                        const uint32_t* __restrict__ meta, int64_t G, int64_t W,
+                                                        const uint32_t* __restrict__ meta,
+                                                        const int32_t* __restrict__ rowidx, int64_t G, int64_t W,
                                                         int64_t steps, int vt, int V, int64_t total,
                                                         char* __restrict__ arec) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= total) return;
   const int lane = (int)(idx % 64);
-  const int tile = (int)((idx / 64) % vt);
-  const int64_t s = (idx / 64 / vt) % steps, b = idx / 64 / vt / steps;
+  const int tile = (int)((idx / 64) % (vt + 1));
+  const int64_t s = (idx / 64 / (vt + 1)) % steps, b = idx / 64 / (vt + 1) / steps;
+  char* rec = arec + (b * steps + s) * ((int64_t)vt * kTileValBytes + kTailBytes);
+  char* tail = rec + vt * kTileValBytes;
+  if (tile == vt) {
+    // row ids of step s + kRidLead, then zero padding (2 dwords per lane cover bytes 512..1023)
+    uint32_t* w = reinterpret_cast<uint32_t*>(tail + kTailRidOff);
+    for (int k = lane; k < (kTailBytes - kTailRidOff) / 4; k += 64) {
+      uint32_t v = 0;
+      if (k < kStepRows && s + kRidLead < steps) v = (uint32_t)rowidx[(b * steps + s + kRidLead) * kStepRows + k];
+      w[k] = v;
+    }
+    if (vt < kMaxTiles)   // unused tile slots of the index words
+      for (int t = vt; t < kMaxTiles; ++t) reinterpret_cast<uint16_t*>(tail)[lane * kMaxTiles + t] = 0;
+    return;
+  }
   const int64_t r = b * V + tile * kTileRows + (lane % 32);
   const int h = lane / 32;
   const int64_t g = s * 8 + 4 * h;
   uint32_t v[4];
   for (int e = 0; e < 4; ++e) v[e] = (g + e < G) ? values[r * G + g + e] : 0u;
-  char* rec = arec + (b * steps + s) * (int64_t)vt * (kTileValBytes + kTileIdxBytes);
   reinterpret_cast<uint4*>(rec + tile * kTileValBytes)[lane] = make_uint4(v[0], v[1], v[2], v[3]);
   const uint32_t word = (s < W) ? (meta[r * W + s] >> (16 * h)) & 0xffffu : 0u;
-  reinterpret_cast<uint32_t*>(rec + vt * kTileValBytes + tile * kTileIdxBytes)[lane] = word;
-}
-
-// Absolute row of B for every gathered row: [R/V][steps][32] (+ readable slack), entry 4*t + p of a
-// step is (8*step + t)*M + column_loc[p]; groups past the end point at row 0 (their values are zero).
-__global__ void __launch_bounds__(256) pack_rowidx_kernel(const uint16_t* __restrict__ columns, int64_t G, int M,
-                                                          int64_t steps, int64_t total, int64_t total_padded,
-                                                          int32_t* __restrict__ rowidx) {
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= total_padded) return;
-  if (idx >= total) { rowidx[idx] = 0; return; }
-  const int rho = (int)(idx % kStepRows);
-  const int64_t s = (idx / kStepRows) % steps, b = idx / kStepRows / steps;
-  const int64_t g = s * 8 + rho / 4;
-  rowidx[idx] = (g < G) ? (int32_t)(g * M + columns[(b * G + g) * kSelCols + (rho % 4)]) : 0;
+  reinterpret_cast<uint16_t*>(tail)[lane * kMaxTiles + tile] = (uint16_t)word;
 }
 
 // packed -> dense: one thread per output element.
@@ -167,10 +183,14 @@ __global__ void __launch_bounds__(256) decompress_kernel(const char* __restrict_
   const int t = (int)(g % 8), h = t / 4, ge = t % 4;
   const int tile = (int)((r % V) / kTileRows);
   const int lane = 32 * h + (int)(r % kTileRows);
-  const char* rec = arec + (b * steps + s) * (int64_t)vt * (kTileValBytes + kTileIdxBytes);
-  const uint32_t word = reinterpret_cast<const uint32_t*>(rec + vt * kTileValBytes + tile * kTileIdxBytes)[lane];
+  const char* rec = arec + (b * steps + s) * ((int64_t)vt * kTileValBytes + kTailBytes);
+  const uint32_t word = reinterpret_cast<const uint16_t*>(rec + vt * kTileValBytes)[lane * kMaxTiles + tile];
   const uint32_t nib = (word >> (4 * ge)) & 0xfu;
-  const int32_t* ri = rowidx + (b * steps + s) * kStepRows + 4 * t;
+  // row ids: from the stream when an earlier record carries them, else from the row-id array
+  const int32_t* ri = (s >= kRidLead)
+      ? reinterpret_cast<const int32_t*>(arec + (b * steps + s - kRidLead) * ((int64_t)vt * kTileValBytes + kTailBytes) +
+                                         vt * kTileValBytes + kTailRidOff) + 4 * t
+      : rowidx + (b * steps + s) * kStepRows + 4 * t;
   const uint16_t* pv = reinterpret_cast<const uint16_t*>(rec + tile * kTileValBytes) + lane * 8 + 2 * ge;
   uint16_t out = 0;
   if (ri[nib & 3] == k) out = pv[0];
@@ -201,15 +221,16 @@ hipError_t launch_compress(const uint16_t* A, int64_t lda, const uint8_t* mask, 
 hipError_t launch_pack(const venom_handle& h, hipStream_t st) {
   const Layout& L = h.lay;
   if (!L.packed || L.R == 0 || L.G == 0) return hipSuccess;
-  int64_t total = L.Rb * L.steps * L.vt * 64;
+  int64_t total = L.Rb * L.steps * kStepRows;
+  hipLaunchKernelGGL(pack_rowidx_kernel, dim3(blocks_for(total)), dim3(256), 0, st,
+                     reinterpret_cast<const uint16_t*>(h.ws + L.off_columns), L.G, h.M, L.steps, total,
+                     reinterpret_cast<int32_t*>(h.ws + L.off_rowidx));
+  total = L.Rb * L.steps * (L.vt + 1) * 64;
   hipLaunchKernelGGL(pack_arec_kernel, dim3(blocks_for(total)), dim3(256), 0, st,
                      reinterpret_cast<const uint32_t*>(h.ws + L.off_values),
-                     reinterpret_cast<const uint32_t*>(h.ws + L.off_meta), L.G, L.W, L.steps, L.vt, h.V, total,
+                     reinterpret_cast<const uint32_t*>(h.ws + L.off_meta),
+                     reinterpret_cast<const int32_t*>(h.ws + L.off_rowidx), L.G, L.W, L.steps, L.vt, h.V, total,
                      h.ws + L.off_arec);
-  total = L.Rb * L.steps * kStepRows;
-  hipLaunchKernelGGL(pack_rowidx_kernel, dim3(blocks_for(total + kRowIdxSlack)), dim3(256), 0, st,
-                     reinterpret_cast<const uint16_t*>(h.ws + L.off_columns), L.G, h.M, L.steps, total,
-                     total + kRowIdxSlack, reinterpret_cast<int32_t*>(h.ws + L.off_rowidx));
   return hipGetLastError();
 }
 

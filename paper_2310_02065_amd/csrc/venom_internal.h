@@ -14,8 +14,10 @@ constexpr int kTileRows = 32;  // rows of one matrix-instruction tile (v_smfmac_
 constexpr int kStepGroups = 8; // groups of M columns consumed per k-step: 8 groups x 4 columns = 32
 constexpr int kStepRows = kStepGroups * kSelCols;  // gathered rows of B per k-step
 constexpr int kTileValBytes = 1024;                // packed values of one 32-row tile for one k-step
-constexpr int kTileIdxBytes = 256;                 // packed index words of one 32-row tile for one k-step
-constexpr int kRowIdxSlack = 256;                  // readable int32 entries past the end of the row-id array
+constexpr int kMaxTiles = 4;                       // the product kernel serves V = 32, 64, 96, 128
+constexpr int kTailBytes = 1024;                   // record tail: index words (512 B), row ids (128 B), padding
+constexpr int kTailRidOff = 512;                   // byte offset of the row ids inside the tail
+constexpr int kRidLead = 3;                        // the tail of record u names the B rows of k-step u + kRidLead
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
