@@ -388,10 +388,10 @@ constexpr int lds_bytes() {
     spmm_kernel<VT, NC, NPB, NA, false>, spmm_kernel<VT, NC, NPB, NA, true> }
 
 static const Variant kVariants[] = {
-    VARIANT("v128_c512", 4, 8, 3, 6), VARIANT("v128_c256", 4, 4, 1, 10), VARIANT("v128_c256_p2", 4, 4, 2, 9), VARIANT("v128_c128", 4, 2, 1, 10),
-    VARIANT("v96_c256", 3, 4, 1, 10),  VARIANT("v96_c128", 3, 2, 1, 10),
-    VARIANT("v64_c512", 2, 8, 3, 10),  VARIANT("v64_c256", 2, 4, 1, 10), VARIANT("v64_c128", 2, 2, 1, 10),
-    VARIANT("v32_c256", 1, 4, 1, 10),  VARIANT("v32_c128", 1, 2, 1, 10),
+    VARIANT("v128_c512", 4, 8, 3, 6), VARIANT("v128_c256", 4, 4, 2, 9), VARIANT("v128_c128", 4, 2, 1, 10),
+    VARIANT("v96_c512", 3, 8, 3, 7),  VARIANT("v96_c256", 3, 4, 2, 10), VARIANT("v96_c128", 3, 2, 1, 10),
+    VARIANT("v64_c512", 2, 8, 3, 10), VARIANT("v64_c256", 2, 4, 2, 10), VARIANT("v64_c128", 2, 2, 1, 10),
+    VARIANT("v32_c512", 1, 8, 3, 10), VARIANT("v32_c256", 1, 4, 2, 10), VARIANT("v32_c128", 1, 2, 1, 10),
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
@@ -399,19 +399,18 @@ int spmm_variant_count() { return kNumVariants; }
 const char* spmm_variant_name(int v) { return (v >= 0 && v < kNumVariants) ? kVariants[v].name : nullptr; }
 
 static int pick_variant(int V, int64_t Ccols, int64_t nbr) {
-  // first listed variant for this V whose tile is not wider than C and that still gives every
-  // CU a workgroup; else the narrowest
-  int narrowest = -1;
+  // the widest column tile that C fills at least half of: wide tiles re-read the A stream least
+  // and measured fastest at every shape tried; narrow C takes the narrow tiles
+  (void)nbr;
+  int best = -1;
   for (int i = 0; i < kNumVariants; ++i) {
     if (kVariants[i].V != V) continue;
-    if (narrowest < 0 || kVariants[i].bsc < kVariants[narrowest].bsc) narrowest = i;
+    if (best < 0) { best = i; continue; }
+    const bool fits_i = 2 * Ccols > kVariants[i].bsc, fits_b = 2 * Ccols > kVariants[best].bsc;
+    if (fits_i && (!fits_b || kVariants[i].bsc > kVariants[best].bsc)) best = i;
+    else if (!fits_i && !fits_b && kVariants[i].bsc < kVariants[best].bsc) best = i;
   }
-  for (int i = 0; i < kNumVariants; ++i) {
-    if (kVariants[i].V != V) continue;
-    const int64_t nct = (Ccols + kVariants[i].bsc - 1) / kVariants[i].bsc;
-    if (Ccols >= kVariants[i].bsc && nct * nbr >= 256) return i;
-  }
-  return narrowest;
+  return best;
 }
 
 venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, int64_t Ccols, void* C, int64_t ldc,
