@@ -45,22 +45,16 @@ struct SpmmParams {
   int nbr, nct;            // block rows, column tiles
   int per_xcd;             // ceil(nbr*nct / 8)
 #ifdef VENOM_ABLATE
-  int ablate;              // experiment switches (never compiled into the product library)
   unsigned long long* trace;
 #endif
 };
 
 #ifdef VENOM_ABLATE
-// timestamps of steps 16..23 go to the last 1.5 KB of LDS (no vector-memory traffic), dumped at the end
-#define TRACE(slot, step, k) do { if (p.trace && blockIdx.x == 8 && lane == 0 && (step) >= 16 && (step) < 24) \
-  reinterpret_cast<unsigned*>(smem + 163840 - 1536)[(((slot) * 8 + (step) - 16) * 4 + (k))] = (unsigned)__builtin_readcyclecounter(); } while (0)
-#define TRACE_DUMP() do { if (p.trace && blockIdx.x == 8) { barrier_only(); if (threadIdx.x < 384) p.trace[threadIdx.x] = reinterpret_cast<unsigned*>(smem + 163840 - 1536)[threadIdx.x]; } } while (0)
-#else
-#define TRACE(slot, step, k) do {} while (0)
+constexpr int kAbl = VENOM_ABLATE;   // experiment switches, fixed at compile time (never in the product library)
 #endif
 constexpr int kNumXcd = 8;
-constexpr int kStages = 4;           // B ring depth; kRidLead == kStages - 1 k-steps are in flight
-static_assert(kRidLead == kStages - 1, "the record tail must name the rows of the step being issued");
+constexpr int kStages = 4;           // B ring depth: three k-steps are in flight
+constexpr int kRidSlots = 16;        // row-id ring: 128 bytes per k-step
 
 // ---- direct-to-LDS loads and their retirement, outside the compiler's wait-count bookkeeping.
 // LDS destination of lane l is lds_addr + l*16; M0 carries lds_addr and needs one wait state
@@ -71,29 +65,22 @@ __device__ __forceinline__ void dma16(const char* base, uint32_t lane_off, uint3
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(base), "s"(lds_addr)
                : "memory");
 }
-// wait until at most N of this wave's loads are outstanding, then meet the other waves
-// wait until at most N of this wave's loads are outstanding, then meet the other waves
-// (ts, experiments only: receives the time between the wait and the barrier)
-template <int N>
-__device__ __forceinline__ void wait_loads_and_barrier(unsigned* ts = nullptr) {
-#ifdef VENOM_ABLATE
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-  if (ts) *ts = (unsigned)__builtin_readcyclecounter();
-  asm volatile("s_barrier" ::: "memory");
-#else
-  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
-#endif
+__device__ __forceinline__ void dma4(const char* base, uint32_t lane_off, uint32_t lds_addr) {  // lane l -> lds_addr + 4*l
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(lane_off), "s"(base), "s"(lds_addr)
+               : "memory");
 }
-// the same with N = k * UNIT for a run-time k in [0, MAXK]
-template <int UNIT, int MAXK, int K = 0>
-__device__ __forceinline__ void wait_units_and_barrier(int k, unsigned* ts = nullptr) {
+// wait until at most N of this wave's loads are outstanding, then meet the other waves
+template <int N>
+__device__ __forceinline__ void wait_loads_and_barrier() {
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+// the same with N = min(k, MAXK) * UNIT for a run-time k >= 0; the steady state (k >= MAXK) is the
+// first case tested
+template <int UNIT, int MAXK>
+__device__ __forceinline__ void wait_units_and_barrier(int k) {
   static_assert(MAXK * UNIT <= 63, "vmcnt is a 6-bit counter");
-  if constexpr (K >= MAXK) {
-    wait_loads_and_barrier<MAXK * UNIT>(ts);
-  } else {
-    if (k == K) wait_loads_and_barrier<K * UNIT>(ts);
-    else wait_units_and_barrier<UNIT, MAXK, K + 1>(k, ts);
-  }
+  if (k >= MAXK) wait_loads_and_barrier<MAXK * UNIT>();
+  else if constexpr (MAXK > 0) wait_units_and_barrier<UNIT, MAXK - 1>(k);
 }
 __device__ __forceinline__ void barrier_only() { asm volatile("s_barrier" ::: "memory"); }
 
@@ -105,11 +92,26 @@ __device__ __forceinline__ floatx16 smfmac(half8 a, half16 b, floatx16 c, int id
   return __builtin_amdgcn_smfmac_f32_32x32x32_f16(a, b, c, idx, 0, ABID);
 }
 
+// This workgroup's share of the tile list.  The grid holds one workgroup per compute unit (the
+// host sizes it) and every workgroup walks several tiles: starting a wide workgroup that owns most
+// of the LDS costs microseconds, and a persistent one can keep its load pipeline full across tile
+// boundaries.  Consecutive workgroup ids land on different XCDs; each XCD takes a contiguous
+// range of the column-tile-major list, so the workgroups of one XCD sweep the same slab of B at
+// the same time and it stays in that L2.
+struct TileWalk {
+  int base, first, stride, count;
+  __device__ __forceinline__ void locate(const SpmmParams& p, int t, int& ct, int& br) const {
+    const int work = base + first + t * stride;
+    ct = work / p.nbr;
+    br = work - ct * p.nbr;
+  }
+};
+
 template <int VT, int NC, int NPB, int NA, bool OUT_F32>
 __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams p) {
   static_assert(NC == 2 || NC == 4 || NC == 8, "consumer waves per workgroup");
   static_assert(VT >= 1 && VT <= kMaxTiles, "32-row tiles per block row");
-  static_assert(NA >= 4, "the A ring holds the record being read, the next one (row ids), and records in flight");
+  static_assert(NA >= 4, "the A ring holds the record being read, the next one, and records in flight");
   constexpr int BSC = 64 * NC;                     // columns of C per workgroup
   constexpr int ROW_BYTES = 2 * BSC;               // one gathered row of B in LDS
   constexpr int RPI = 1024 / ROW_BYTES;            // rows written by one wave-wide 16-byte load
@@ -118,63 +120,108 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
   constexpr int NBH = (NI + NPB - 1) / NPB, NBL = NI / NPB, NBHI = NI % NPB;  // ... per B producer
   constexpr int B_BYTES = kStepRows * ROW_BYTES;
   constexpr int A_BYTES = VT * kTileValBytes + kTailBytes;   // one A record
-  constexpr int T_OFF = VT * kTileValBytes;        // record tail: index words, row ids
-  constexpr int ARING = kStages * B_BYTES;         // LDS: [B ring][A ring]
+  constexpr int T_OFF = VT * kTileValBytes;        // record tail: index words
+  constexpr int ARING = kStages * B_BYTES;         // LDS: [B ring][A ring][row-id ring]
+  constexpr int RIDRING = ARING + NA * A_BYTES;
   constexpr int NJ = VT + 1;                       // A loads per k-step: VT value blocks + the tail
   constexpr int PA = NA - 1;                       // k-steps the A stream runs ahead
-  constexpr int CROW = 64 + 8;                     // halfs per staged output row (padded)
-  static_assert((kStages - 2) * NBH <= 63 && PA * NJ <= 63, "load counts");
+  constexpr int PB = kStages - 1;                  // k-steps the B stream runs ahead
+  static_assert((kStages - 2) * NBH <= 63 && PA * NJ <= 63, "load counts fit the 6-bit counter");
+  static_assert(NC * 4096 <= B_BYTES, "the output staging of all consumers fits one B stage");
+  constexpr int RA = PA + PB + 1;                  // k-steps the row-id stream runs ahead: the ids of step
+                                                   // g+PB+1 are then older than record g+1 in the load queue
+  static_assert(kRidSlots >= RA - PB + 2, "a row-id slot is rewritten only after its last reader");
 
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(LDS_PTR(char))smem;
-
-  // ---- which block of C: consecutive workgroup ids land on different XCDs; give each XCD a
-  // contiguous range of the column-tile-major work list.
-  const int xcd = blockIdx.x % kNumXcd;
-  const int work = xcd * p.per_xcd + blockIdx.x / kNumXcd;
-  if (work >= p.nbr * p.nct) return;
-  const int ct = work / p.nbr, br = work % p.nbr;
-
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
+#ifdef VENOM_ABLATE
+  if (p.trace && threadIdx.x == 0 && blockIdx.x < 16) {
+    p.trace[blockIdx.x * 4 + 0] = __builtin_readcyclecounter();
+    p.trace[blockIdx.x * 4 + 1] = wall_clock64();
+  }
+#endif
+  TileWalk tw;
+  {
+    const int xcd = blockIdx.x % kNumXcd;
+    tw.base = xcd * p.per_xcd;
+    tw.first = blockIdx.x / kNumXcd;
+    tw.stride = gridDim.x / kNumXcd;
+    int lim = p.nbr * p.nct - tw.base;
+    if (lim > p.per_xcd) lim = p.per_xcd;
+    tw.count = lim > tw.first ? (lim - tw.first + tw.stride - 1) / tw.stride : 0;
+  }
+  if (tw.count == 0) return;                       // the whole workgroup leaves together
+  // All k-steps of all tiles of this workgroup form one sequence g = 0 .. G-1; the rings and the
+  // barriers are indexed by g, so the loads of the next tile start while this one is finishing.
+  // Barriers, in order: one before the first step (the first row ids are on chip), one per step
+  // ("step g is complete in LDS, step g-1 is consumed"), and one more after the last step of each
+  // tile, after which the consumers stage their output in the B stage they have just drained.
+  const int G = tw.count * p.steps;
+
   if (wave == NC + NPB) {
     // ========================================================================= A producer
-    const char* arec = p.arec + (int64_t)br * p.steps * p.rec_bytes;
+    // Streams, in one in-order queue: the packed records, PA steps ahead, and the row ids of B
+    // that the gather producers need, RA steps ahead, into a ring of kRidSlots x 128 bytes.
     const uint32_t lane_off = lane * 16;
-    auto issue = [&](int u) {
+    int ct, br;
+    // record stream position
+    int a_t = 0, a_s = 0, a_slot = 0;
+    tw.locate(p, 0, ct, br);
+    const char* a_ptr = p.arec + (int64_t)br * p.steps * p.rec_bytes;
+    auto next_record = [&]() {
 #ifdef VENOM_ABLATE
-      if (p.ablate & 8) return;
+      if (!(kAbl & (8 | 1024)))
 #endif
-      const uint32_t dst = lds0 + ARING + (u % NA) * A_BYTES;
-      const char* rec = arec + (int64_t)u * p.rec_bytes;
+      {
+        const uint32_t dst = lds0 + ARING + a_slot * A_BYTES;
 #pragma unroll
-      for (int j = 0; j < NJ; ++j) dma16(rec + j * 1024, lane_off, dst + j * 1024);
+        for (int j = 0; j < NJ; ++j) dma16(a_ptr + j * 1024, lane_off, dst + j * 1024);
+      }
+      a_ptr += p.rec_bytes;
+      a_slot = a_slot + 1 == NA ? 0 : a_slot + 1;
+      if (++a_s == p.steps) {
+        a_s = 0;
+        if (++a_t < tw.count) {
+          tw.locate(p, a_t, ct, br);
+          a_ptr = p.arec + (int64_t)br * p.steps * p.rec_bytes;
+        }
+      }
     };
-    for (int j = 0; j < PA; ++j)
-      if (j < p.steps) issue(j);
-    for (int s = 0; s < p.steps; ++s) {
-      // records s and s+1 have landed when at most the records of the steps after s+1 are pending
-      // (the B producers read the row ids in record s+1 one step early)
-      const int left = p.steps - 2 - s;
-      TRACE(0, s, 0);
-      unsigned ts = 0;
-      wait_units_and_barrier<NJ, PA - 2>(left < 0 ? 0 : (left < PA - 2 ? left : PA - 2), &ts);
-#ifdef VENOM_ABLATE
-      if (p.trace && blockIdx.x == 8 && lane == 0 && s >= 16 && s < 24) reinterpret_cast<unsigned*>(smem + 163840 - 1536)[((0 * 8 + s - 16) * 4 + 3)] = ts;
-#endif
-      TRACE(0, s, 1);
-      // after the barrier everyone is done with record s-1: its slot takes record s+PA
-      if (s + PA < p.steps) issue(s + PA);
-      TRACE(0, s, 2);
+    // row-id stream position
+    int r_t = 0, r_s = 0, r_slot = 0;
+    const char* r_ptr = reinterpret_cast<const char*>(p.rowidx) + (int64_t)br * p.steps * (kStepRows * 4);
+    auto next_rowids = [&]() {
+      if (lane < kStepRows) dma4(r_ptr, lane * 4, lds0 + RIDRING + r_slot * (kStepRows * 4));
+      r_ptr += kStepRows * 4;
+      r_slot = (r_slot + 1) % kRidSlots;
+      if (++r_s == p.steps) {
+        r_s = 0;
+        if (++r_t < tw.count) {
+          int ct2, br2;
+          tw.locate(p, r_t, ct2, br2);
+          r_ptr = reinterpret_cast<const char*>(p.rowidx) + (int64_t)br2 * p.steps * (kStepRows * 4);
+        }
+      }
+    };
+    int first_records = 0;
+    for (int j = 0; j < RA && j < G; ++j) next_rowids();
+    for (int j = 0; j < PA && j < G; ++j, ++first_records) next_record();
+    wait_units_and_barrier<NJ, PA>(first_records);  // the row ids (older than every record) have landed
+    int c_s = 0;                                   // step inside the tile the consumers are on
+    for (int g = 0; g < G; ++g) {
+      // records g and g+1 have landed when at most the records after g+1 are pending; the row-id
+      // loads in between only make the wait a little stricter
+      const int left = G - 2 - g;
+      wait_units_and_barrier<NJ, PA - 2>(left < 0 ? 0 : left);
+      // after the barrier everyone is done with record g-1: its slot takes record g+PA
+      if (g + PA < G) next_record();
+      if (g + RA < G) next_rowids();
+      if (++c_s == p.steps) { c_s = 0; barrier_only(); }
     }
-    wait_loads_and_barrier<0>();                   // the consumers' last barrier
-#ifdef VENOM_ABLATE
-    TRACE_DUMP();
-#endif
-    return;
-  }
-  if (wave >= NC) {
+  } else if (wave >= NC) {
     // ========================================================================= B producers
     const int pj = wave - NC;
     // B load q of this producer is load number pj + NPB*q of the k-step; it covers rows
@@ -183,186 +230,214 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
     // The row ids of a k-step sit in lane order in one register (lane l holds row l%32); the rows
     // of one load are picked out with v_readlane and the byte offset of a lane is
     // row * ldb_bytes + column offset, a 24-bit multiply-add (the host checks the ranges).
-    uint32_t ld_col[NBH];
+    int chunk_col[NBH];                            // first column of this lane's chunk inside the tile
 #pragma unroll
     for (int q = 0; q < NBH; ++q) {
       const int rho = ((pj + NPB * q) % NI) * RPI + lane / LPR;
-      const int chunk = (lane % LPR) ^ slot_swizzle(rho);
-      int64_t col = (int64_t)ct * BSC + chunk * 8;
-      if (col + 8 > p.Ccols) col = p.Ccols - 8;    // past the edge: any in-bounds data, never stored
-      ld_col[q] = (uint32_t)(col * 2);
+      chunk_col[q] = ((lane % LPR) ^ slot_swizzle(rho)) * 8;
     }
-    const int rowsel = lane / LPR;                 // which of the RPI rows of a load this lane writes
-    const uint32_t ldb24 = (uint32_t)p.ldb_bytes;
-    const int32_t* ridx = p.rowidx + (int64_t)br * p.steps * kStepRows;
-    const bool hi = NBHI == 0 || pj < NBHI;        // this producer has NBH loads per k-step, else NBL
-
-    auto issue = [&](int u, int ridv) {
-#ifdef VENOM_ABLATE
-      if (p.ablate & 8) return;
-#endif
-      const uint32_t sb = lds0 + (u % kStages) * B_BYTES;
+    uint32_t ld_col[NBH];
+    auto set_tile = [&](int t) {
+      int ct, br;
+      tw.locate(p, t, ct, br);
 #pragma unroll
       for (int q = 0; q < NBH; ++q) {
-        if (q < NBL || hi) {
-          const int rho0 = ((pj + NPB * q) % NI) * RPI;
-          int row = __builtin_amdgcn_readlane(ridv, rho0);
-#pragma unroll
-          for (int k = 1; k < RPI; ++k) {
-            const int rk = __builtin_amdgcn_readlane(ridv, rho0 + k);
-            row = rowsel == k ? rk : row;
-          }
-          dma16(p.B, __umul24((uint32_t)row, ldb24) + ld_col[q], sb + (pj + NPB * q) * 1024);
-        }
+        int64_t col = (int64_t)ct * BSC + chunk_col[q];
+        if (col + 8 > p.Ccols) col = p.Ccols - 8;  // past the edge: any in-bounds data, never stored
+        ld_col[q] = (uint32_t)(col * 2);
       }
     };
-
-    // prologue: the first two k-steps (row ids straight from global memory)
-#pragma unroll
-    for (int j = 0; j < kRidLead; ++j) {
-      if (j < p.steps) issue(j, ridx[j * kStepRows + (lane & 31)]);
-    }
-    int ridv = 0;                                  // row ids of the k-step issued next
-    for (int s = 0; s < p.steps; ++s) {
-      // this producer's part of k-step s has landed when at most its loads of the later steps
-      // (up to two) are pending
-      const int left = p.steps - 1 - s;
-      const int pend = left < kStages - 2 ? left : kStages - 2;
-      TRACE(1 + pj, s, 0);
-      unsigned ts = 0;
-      if (hi) wait_units_and_barrier<NBH, kStages - 2>(pend, &ts);
-      else wait_units_and_barrier<NBL, kStages - 2>(pend, &ts);
-      TRACE(1 + pj, s, 1);
-      // after the barrier: A records s and s+1 are on chip, and the consumers are done with B stage s-1
-      if (s + kRidLead < p.steps) {
-        if (s == 0) ridv = *reinterpret_cast<const int*>(smem + ARING + T_OFF + kTailRidOff + (lane & 31) * 4);
-        TRACE(1 + pj, s, 2);
-        issue(s + kRidLead, ridv);
-        if (s + 1 + kRidLead < p.steps)            // row ids for the next iteration, from record s+1
-          ridv = *reinterpret_cast<const int*>(smem + ARING + ((s + 1) % NA) * A_BYTES + T_OFF + kTailRidOff +
-                                               (lane & 31) * 4);
-      }
+    const int rowsel = lane / LPR;                 // which of the RPI rows of a load this lane writes
+    const uint32_t ldb24 = (uint32_t)p.ldb_bytes;
+    const bool hi = NBHI == 0 || pj < NBHI;        // this producer has NBH loads per k-step, else NBL
+    int b_t = 0, b_s = 0, b_slot = 0;
+    set_tile(0);
+    auto issue = [&](int ridv) {
 #ifdef VENOM_ABLATE
-      if (p.trace && blockIdx.x == 8 && lane == 0 && s >= 16 && s < 24) reinterpret_cast<unsigned*>(smem + 163840 - 1536)[(((1 + pj) * 8 + s - 16) * 4 + 3)] = ts;
+      if (!(kAbl & (8 | 2048)))
 #endif
-    }
-    wait_loads_and_barrier<0>();                   // the consumers' last barrier
-#ifdef VENOM_ABLATE
-    TRACE_DUMP();
-#endif
-    return;
-  }
-
-  // ============================================================================= consumer
-  // Transposing LDS reads that build the B operand.  Sub-read cb of a 32-column tile: lane block
-  // blk = lane/16 reads group t = 4*(cb/2) + 2*(blk/2) + cb%2, 16-column window 2*tile + blk%2;
-  // inside the block lane i reads row 4*t + i/4, 8-byte piece i%4.
-  int rd_off[2][4];
-  {
-    const int blk = lane >> 4, i = lane & 15, e = i >> 2, c8 = i & 3;
+      {
+        const uint32_t sb = lds0 + b_slot * B_BYTES;
 #pragma unroll
-    for (int tc = 0; tc < 2; ++tc)
+        for (int q = 0; q < NBH; ++q) {
+          if (q < NBL || hi) {
+            const int rho0 = ((pj + NPB * q) % NI) * RPI;
+            int row = __builtin_amdgcn_readlane(ridv, rho0);
 #pragma unroll
-      for (int cb = 0; cb < 4; ++cb) {
-        const int t = 4 * (cb >> 1) + 2 * (blk >> 1) + (cb & 1);
-        const int rho = 4 * t + e;
-        const int win = wave * 4 + tc * 2 + (blk & 1);
-        const int slot = (2 * win + (c8 >> 1)) ^ slot_swizzle(rho);
-        rd_off[tc][cb] = rho * ROW_BYTES + slot * 16 + (c8 & 1) * 8;
-      }
-  }
-
-  floatx16 acc[VT][2];
-#pragma unroll
-  for (int tr = 0; tr < VT; ++tr)
-#pragma unroll
-    for (int tc = 0; tc < 2; ++tc)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[tr][tc][v] = 0.f;
-
-  for (int s = 0; s < p.steps; ++s) {
-    TRACE(4 + wave, s, 0);
-    barrier_only();                                // stage s is complete
-    TRACE(4 + wave, s, 1);
-#ifdef VENOM_ABLATE
-    if (p.ablate & 4) continue;
-#endif
-    const char* sb = smem + (s % kStages) * B_BYTES;
-    const char* sa = smem + ARING + (s % NA) * A_BYTES;
-    half16 bf[2];
-#pragma unroll
-    for (int tc = 0; tc < 2; ++tc)
-#pragma unroll
-      for (int cb = 0; cb < 4; ++cb) {
-        const short4v piece = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(short4v))(sb + rd_off[tc][cb]));
-        const half4 ph = __builtin_bit_cast(half4, piece);
-        bf[tc][4 * cb + 0] = ph[0]; bf[tc][4 * cb + 1] = ph[1]; bf[tc][4 * cb + 2] = ph[2]; bf[tc][4 * cb + 3] = ph[3];
-      }
-    const uint2 ixw = *reinterpret_cast<const uint2*>(sa + T_OFF + lane * 8);   // 4 x 16 index bits
-#pragma unroll
-    for (int tr = 0; tr < VT; ++tr) {
-      const half8 av = *reinterpret_cast<const half8*>(sa + tr * kTileValBytes + lane * 16);
-      const int ix = (int)((tr >> 1) ? ixw.y : ixw.x);
-#pragma unroll
-      for (int tc = 0; tc < 2; ++tc) {
-        if (tr & 1) acc[tr][tc] = smfmac<1>(av, bf[tc], acc[tr][tc], ix);
-        else acc[tr][tc] = smfmac<0>(av, bf[tc], acc[tr][tc], ix);
-      }
-    }
-    TRACE(4 + wave, s, 2);
-  }
-  barrier_only();                                  // every consumer is done reading the ring
-#ifdef VENOM_ABLATE
-  TRACE_DUMP();
-#endif
-
-  // ---- stage 3: registers -> (LDS) -> global.  Accumulator element v of a 32x32 tile sits at
-  // row 8*(v/4) + 4*(lane/32) + v%4, column lane%32.
-#ifdef VENOM_ABLATE
-  if ((p.ablate & 16) && acc[0][0][0] != 12345.f) return;
-#endif
-  const int64_t row0 = (int64_t)br * VT * 32;
-  const int64_t col0 = (int64_t)ct * BSC + wave * 64;
-  if constexpr (OUT_F32) {
-    float* Cf = reinterpret_cast<float*>(p.C);
-#pragma unroll
-    for (int tr = 0; tr < VT; ++tr)
-#pragma unroll
-      for (int tc = 0; tc < 2; ++tc) {
-        const int64_t col = col0 + tc * 32 + (lane & 31);
-        if (col < p.Ccols) {
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int64_t row = row0 + tr * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-            Cf[row * p.ldc + col] = acc[tr][tc][v];
+            for (int k = 1; k < RPI; ++k) {
+              const int rk = __builtin_amdgcn_readlane(ridv, rho0 + k);
+              row = rowsel == k ? rk : row;
+            }
+            dma16(p.B, __umul24((uint32_t)row, ldb24) + ld_col[q], sb + (pj + NPB * q) * 1024);
           }
         }
       }
+      b_slot = (b_slot + 1) % kStages;
+      if (++b_s == p.steps) {
+        b_s = 0;
+        if (++b_t < tw.count) set_tile(b_t);
+      }
+    };
+    auto rowids_of = [&](int g) {
+      return *reinterpret_cast<const int*>(smem + RIDRING + (g % kRidSlots) * (kStepRows * 4) + (lane & 31) * 4);
+    };
+    barrier_only();                                // the first row ids are on chip
+    for (int j = 0; j < PB && j < G; ++j) issue(rowids_of(j));
+    int ridv = PB < G ? rowids_of(PB) : 0;         // row ids of the k-step issued next
+    int c_s = 0;
+    for (int g = 0; g < G; ++g) {
+      // this producer's part of k-step g has landed when at most its loads of the later steps
+      // (up to two) are pending
+      const int left = G - 1 - g;
+      if (hi) wait_units_and_barrier<NBH, kStages - 2>(left);
+      else wait_units_and_barrier<NBL, kStages - 2>(left);
+      // after the barrier the consumers are done with stage g-1: it takes step g+PB
+      if (g + PB < G) {
+        issue(ridv);
+        if (g + PB + 1 < G) ridv = rowids_of(g + PB + 1);
+      }
+      if (++c_s == p.steps) { c_s = 0; barrier_only(); }
+    }
   } else {
-    _Float16* cl = reinterpret_cast<_Float16*>(smem) + wave * (VT * 32 * CROW);   // this wave's strip
+    // ========================================================================= consumers
+    // Transposing LDS reads that build the B operand.  Sub-read cb of a 32-column tile: lane block
+    // blk = lane/16 reads group t = 4*(cb/2) + 2*(blk/2) + cb%2, 16-column window 2*tile + blk%2;
+    // inside the block lane i reads row 4*t + i/4, 8-byte piece i%4.
+    int rd_off[2][4];
+    {
+      const int blk = lane >> 4, i = lane & 15, e = i >> 2, c8 = i & 3;
 #pragma unroll
-    for (int tr = 0; tr < VT; ++tr)
+      for (int tc = 0; tc < 2; ++tc)
 #pragma unroll
-      for (int tc = 0; tc < 2; ++tc) {
-        const int col = tc * 32 + (lane & 31);
+        for (int cb = 0; cb < 4; ++cb) {
+          const int t = 4 * (cb >> 1) + 2 * (blk >> 1) + (cb & 1);
+          const int rho = 4 * t + e;
+          const int win = wave * 4 + tc * 2 + (blk & 1);
+          const int slot = (2 * win + (c8 >> 1)) ^ slot_swizzle(rho);
+          rd_off[tc][cb] = rho * ROW_BYTES + slot * 16 + (c8 & 1) * 8;
+        }
+    }
+    int b_slot = 0, a_slot = 0;
+    barrier_only();                                // (the producers' start-up barrier)
+    for (int t = 0; t < tw.count; ++t) {
+      floatx16 acc[VT][2];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = tr * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-          cl[row * CROW + col] = (_Float16)acc[tr][tc][v];  // one rounding, nearest-even
+      for (int tr = 0; tr < VT; ++tr)
+#pragma unroll
+        for (int tc = 0; tc < 2; ++tc)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc[tr][tc][v] = 0.f;
+
+      const char* sb = smem;
+      for (int s = 0; s < p.steps; ++s) {
+        barrier_only();                            // this k-step is complete in LDS
+        sb = smem + b_slot * B_BYTES;
+        const char* sa = smem + ARING + a_slot * A_BYTES;
+        b_slot = (b_slot + 1) % kStages;
+        a_slot = a_slot + 1 == NA ? 0 : a_slot + 1;
+#ifdef VENOM_ABLATE
+        if (kAbl & 4) continue;
+        constexpr bool no_lds = kAbl & 64;         // matrix instructions on whatever the registers hold
+#else
+        constexpr bool no_lds = false;
+#endif
+        half16 bf[2];
+        if (no_lds) asm volatile("" : "=v"(bf[0]), "=v"(bf[1]));
+        else
+#pragma unroll
+        for (int tc = 0; tc < 2; ++tc)
+#pragma unroll
+          for (int cb = 0; cb < 4; ++cb) {
+            const short4v piece = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(short4v))(sb + rd_off[tc][cb]));
+            const half4 ph = __builtin_bit_cast(half4, piece);
+            bf[tc][4 * cb + 0] = ph[0]; bf[tc][4 * cb + 1] = ph[1]; bf[tc][4 * cb + 2] = ph[2]; bf[tc][4 * cb + 3] = ph[3];
+          }
+        uint2 ixw;                                 // 4 x 16 index bits
+        if (no_lds) asm volatile("" : "=v"(ixw));
+        else ixw = *reinterpret_cast<const uint2*>(sa + T_OFF + lane * 8);
+#pragma unroll
+        for (int tr = 0; tr < VT; ++tr) {
+          half8 av;
+          if (no_lds) asm volatile("" : "=v"(av));
+          else av = *reinterpret_cast<const half8*>(sa + tr * kTileValBytes + lane * 16);
+          const int ix = (int)((tr >> 1) ? ixw.y : ixw.x);
+#ifdef VENOM_ABLATE
+          if (kAbl & 32) {                         // LDS reads only
+            asm volatile("" ::"v"(av), "v"(bf[0]), "v"(bf[1]), "v"(ix));
+            continue;
+          }
+#endif
+#pragma unroll
+          for (int tc = 0; tc < 2; ++tc) {
+            if (tr & 1) acc[tr][tc] = smfmac<1>(av, bf[tc], acc[tr][tc], ix);
+            else acc[tr][tc] = smfmac<0>(av, bf[tc], acc[tr][tc], ix);
+          }
         }
       }
-    // the same wave reads its own strip back: 8 lanes x 16 B per row, 8 rows per pass
-    _Float16* Ch = reinterpret_cast<_Float16*>(p.C);
-    const int chunk = lane & 7, rsub = lane >> 3;
-    const int64_t col = col0 + chunk * 8;
-    if (col < p.Ccols) {
-#pragma unroll 4
-      for (int r = rsub; r < VT * 32; r += 8) {
-        const uint4 val = *reinterpret_cast<const uint4*>(cl + r * CROW + chunk * 8);
-        *reinterpret_cast<uint4*>(Ch + (row0 + r) * p.ldc + col) = val;
+      barrier_only();                              // every consumer has drained the last B stage
+
+      // ---- stage 3: registers -> (LDS) -> global.  Accumulator element v of a 32x32 tile sits
+      // at row 8*(v/4) + 4*(lane/32) + v%4, column lane%32.
+#ifdef VENOM_ABLATE
+      if ((kAbl & 16) && acc[0][0][0] != 12345.f) continue;
+#endif
+      int ct, br;
+      tw.locate(p, t, ct, br);
+      const int64_t row0 = (int64_t)br * VT * 32;
+      const int64_t col0 = (int64_t)ct * BSC + wave * 64;
+      if constexpr (OUT_F32) {
+        float* Cf = reinterpret_cast<float*>(p.C);
+#pragma unroll
+        for (int tr = 0; tr < VT; ++tr)
+#pragma unroll
+          for (int tc = 0; tc < 2; ++tc) {
+            const int64_t col = col0 + tc * 32 + (lane & 31);
+            if (col < p.Ccols) {
+#pragma unroll
+              for (int v = 0; v < 16; ++v) {
+                const int64_t row = row0 + tr * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                Cf[row * p.ldc + col] = acc[tr][tc][v];
+              }
+            }
+          }
+      } else {
+        // One 32 x 64 tile row at a time through this wave's 4 KB of the drained stage (the
+        // producers refill that stage only after the next barrier).  A staged row is 128 bytes;
+        // its 16-byte chunks are XOR-swizzled by bit 2 of the row so that the two half-waves,
+        // which write rows r and r+4, use different banks.
+        char* stg = const_cast<char*>(sb) + wave * 4096;
+        _Float16* Ch = reinterpret_cast<_Float16*>(p.C);
+        const int chunk = lane & 7, rsub = lane >> 3;
+        const int64_t col = col0 + chunk * 8;
+#pragma unroll
+        for (int tr = 0; tr < VT; ++tr) {
+#pragma unroll
+          for (int tc = 0; tc < 2; ++tc) {
+            const int c = tc * 32 + (lane & 31);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int r = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+              const int sw = ((c >> 3) ^ (4 * ((r >> 2) & 1)));
+              *reinterpret_cast<_Float16*>(stg + r * 128 + sw * 16 + (c & 7) * 2) =
+                  (_Float16)acc[tr][tc][v];        // one rounding, nearest-even
+            }
+          }
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int r = i * 8 + rsub;
+            const uint4 val = *reinterpret_cast<const uint4*>(stg + r * 128 + ((chunk ^ (4 * ((r >> 2) & 1))) * 16));
+            if (col < p.Ccols) *reinterpret_cast<uint4*>(Ch + (row0 + tr * 32 + r) * p.ldc + col) = val;
+          }
+        }
       }
     }
   }
+#ifdef VENOM_ABLATE
+  if (p.trace && threadIdx.x == 0 && blockIdx.x < 16) {
+    p.trace[blockIdx.x * 4 + 2] = __builtin_readcyclecounter();
+    p.trace[blockIdx.x * 4 + 3] = wall_clock64();
+  }
+#endif
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -377,10 +452,8 @@ struct Variant {
 };
 
 template <int VT, int NC, int NA>
-constexpr int lds_bytes() {
-  const int ring = kStages * kStepRows * 128 * NC + NA * (VT * kTileValBytes + kTailBytes);
-  const int epi = NC * VT * 32 * (64 + 8) * 2;
-  return ring > epi ? ring : epi;
+constexpr int lds_bytes() {   // B ring, A ring, row-id ring (the output staging reuses a B stage)
+  return kStages * kStepRows * 128 * NC + NA * (VT * kTileValBytes + kTailBytes) + kRidSlots * kStepRows * 4;
 }
 
 #define VARIANT(NAME, VT, NC, NPB, NA)                                                         \
@@ -429,11 +502,10 @@ venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, in
   p.ldb_bytes = ldb * 2; p.ldc = ldc; p.Ccols = Ccols; p.rec_bytes = L.rec_bytes;
   p.steps = (int)L.steps;
 #ifdef VENOM_ABLATE
-  p.ablate = getenv("VENOM_ABLATE") ? atoi(getenv("VENOM_ABLATE")) : 0;
   static unsigned long long* trace_buf = nullptr;
+  static int trace_calls = 0;
   if (getenv("VENOM_TRACE")) {
-    if (!trace_buf) { hipMalloc(&trace_buf, 16 * 64 * 4 * 8); }
-    hipMemsetAsync(trace_buf, 0, 16 * 64 * 4 * 8, st);
+    if (!trace_buf) hipMalloc(&trace_buf, 64 * 8);
     p.trace = trace_buf;
   }
 #endif
@@ -445,13 +517,22 @@ venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, in
     return VENOM_ERR_UNSUPPORTED;
   p.nbr = (int)L.Rb; p.nct = (int)nct;
   p.per_xcd = (int)((total + kNumXcd - 1) / kNumXcd);
-  const unsigned grid = (unsigned)(p.per_xcd * kNumXcd);
+  // one resident workgroup per compute unit (two where the tile is small enough to share a unit);
+  // each walks per_xcd / (grid / 8) tiles
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < kNumXcd)
+    return VENOM_ERR_HIP;
+  const int share = (var.lds <= 80 * 1024 && var.threads <= 512) ? 2 : 1;
+  const int64_t resident_per_xcd = (int64_t)(cus / kNumXcd) * share;
+  const int64_t wg_per_xcd = p.per_xcd < resident_per_xcd ? p.per_xcd : resident_per_xcd;
+  const unsigned grid = (unsigned)(wg_per_xcd * kNumXcd);
+  // a workgroup numbers the k-steps of all its tiles with one 32-bit counter
+  if ((p.per_xcd + wg_per_xcd - 1) / wg_per_xcd * L.steps >= ((int64_t)1 << 30)) return VENOM_ERR_UNSUPPORTED;
   auto fn = c_dtype == 1 ? var.f32 : var.f16;
   if (var.lds > 64 * 1024) {
     // opting in to more than 64 KB of dynamic LDS is a per-function attribute (set once per device)
     static bool opted_in[kNumVariants][2][16] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return VENOM_ERR_HIP;
     if (dev < 0 || dev >= 16 || !opted_in[variant][c_dtype][dev]) {
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
                               var.lds) != hipSuccess)
@@ -459,25 +540,17 @@ venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, in
       if (dev >= 0 && dev < 16) opted_in[variant][c_dtype][dev] = true;
     }
   }
-#ifdef VENOM_ABLATE
-  const int launch_lds = 163840;   // room for the timestamp area
-  hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, launch_lds);
-#else
   const int launch_lds = var.lds;
-#endif
   hipLaunchKernelGGL(fn, dim3(grid), dim3(var.threads), launch_lds, st, p);
 #ifdef VENOM_ABLATE
-  if (p.trace) {
+  if (p.trace && ++trace_calls == atoi(getenv("VENOM_TRACE"))) {
     hipStreamSynchronize(st);
-    static unsigned long long host[384];
+    unsigned long long host[64];
     hipMemcpy(host, p.trace, sizeof(host), hipMemcpyDeviceToHost);
-    FILE* f = fopen(getenv("VENOM_TRACE"), "w");
-    if (f) {
-      for (int slot = 0; slot < 12; ++slot) for (int st_ = 0; st_ < 8; ++st_) {
-        const unsigned long long* e = host + (slot * 8 + st_) * 4;
-        if (e[0] | e[1] | e[2] | e[3]) fprintf(f, "%d %d %llu %llu %llu %llu\n", slot, st_ + 16, e[0], e[1], e[2], e[3]);
-      }
-      fclose(f);
+    for (int b = 0; b < 16; b += 5) {
+      const double cyc = (double)(host[b * 4 + 2] - host[b * 4 + 0]), ref = (double)(host[b * 4 + 3] - host[b * 4 + 1]);
+      fprintf(stderr, "wg %d: %.0f shader ticks, %.0f ref ticks (100 MHz) -> %.3f us, %.1f MHz\n", b, cyc, ref, ref / 100.0,
+              cyc / ref * 100.0);
     }
   }
 #endif
