@@ -31,7 +31,7 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/),
 # scaled by the same counters read on a plain copy kernel; None where not measured yet.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {"gpt3": 1202692096}   # 998.7 MB read + 203.9 MB written
 
 
 def algorithmic_bytes(R, K, C, V, M, out_bytes=2):
@@ -50,6 +50,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch three plain 1 GiB device copies (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives or sharding are part of it); "
@@ -170,6 +172,15 @@ def main():
                                "kind": "oracle",
                                "sample": f"first {rows} of {R} rows of the same workload (expand to dense + fp64 "
                                          f"matmul for C* and the bound matrix), {t_cpu:.2f} s"}
+    if args.copy_calibration:
+        # a plain copy kernel of known size: 2^30 bytes read, 2^30 bytes written per launch
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["copy_calibration"] = {"bytes_read": 1 << 30, "bytes_written": 1 << 30, "launches": 3}
+        del src, dst
     out["host_seconds"] = {"generate_inputs": round(t_gen, 1)}
     print(json.dumps(out))
 
