@@ -43,7 +43,7 @@ typedef enum {
   VENOM_ERR_INVALID_ARG = 1, /* NULL where a pointer is required, negative size, bad enum value      */
   VENOM_ERR_SHAPE = 2,       /* R % V, K % M, M < 4, V < 1, C_cols < 1, leading dimension too small  */
   VENOM_ERR_UNSUPPORTED = 3, /* N != 2; misaligned pointer / leading dimension; shape the kernel does
-                                not cover (venom_spmm needs V % 32 == 0 and C_cols % 8 == 0)         */
+                                not cover (venom_spmm needs V in {32,64,96,128}, C_cols % 8 == 0)   */
   VENOM_ERR_MASK_COLS = 4,   /* illegal mask: a V x M block uses more than 4 columns                 */
   VENOM_ERR_MASK_ROW = 5,    /* illegal mask: a row keeps more than 2 entries in a group of M        */
   VENOM_ERR_WORKSPACE = 6,   /* workspace NULL, misaligned (256 B) or smaller than required          */
@@ -89,7 +89,7 @@ venom_status_t venom_export(const venom_handle_t* h, uint16_t* values_dev, uint1
 
 /* Section 3 read backwards: expand to the dense masked R x K fp16 matrix (+0 outside the
  * structure), lda >= K.  Reads the KERNEL's packed copies, so it also checks the packing.
- * Needs V % 32 == 0 (else VENOM_ERR_UNSUPPORTED).  Asynchronous on `stream`. */
+ * Needs V in {32, 64, 96, 128} (else VENOM_ERR_UNSUPPORTED).  Asynchronous on `stream`. */
 venom_status_t venom_decompress(const venom_handle_t* h, void* A_f16_dev, int64_t lda, void* stream);
 
 /* Section 4 (stages 1-3 of the kernel design; figure 4 for the mapping onto the 2:4 matrix
@@ -97,7 +97,8 @@ venom_status_t venom_decompress(const venom_handle_t* h, void* A_f16_dev, int64_
  *   B_f16_dev   K x C_cols fp16, ldb >= C_cols
  *   C_dev       R x C_cols, fp16 (c_dtype 0, rounded once from the fp32 accumulator, nearest-even)
  *               or fp32 (c_dtype 1), ldc >= C_cols; must not overlap B
- * B, C and both leading dimensions must be 16-byte aligned; V % 32 == 0; C_cols % 8 == 0.
+ * B, C and both leading dimensions must be 16-byte aligned; V in {32, 64, 96, 128}; C_cols % 8 == 0;
+ * K < 2^24, ldb < 2^23 and K * ldb < 2^31 (32-bit gather offsets).
  * Asynchronous on `stream`, allocates nothing, bitwise repeatable (no atomics, no split K). */
 venom_status_t venom_spmm(const venom_handle_t* h, const void* B_f16_dev, int64_t ldb, int64_t C_cols,
                           void* C_dev, int64_t ldc, int c_dtype, void* stream);
@@ -108,7 +109,7 @@ venom_status_t venom_spmm(const venom_handle_t* h, const void* B_f16_dev, int64_
 venom_status_t venom_spmm_variant(const venom_handle_t* h, const void* B_f16_dev, int64_t ldb, int64_t C_cols,
                                   void* C_dev, int64_t ldc, int c_dtype, int variant, void* stream);
 int venom_spmm_variant_count(void);
-/* Name of a variant ("v128_c256_w2x2", ...) or NULL. */
+/* Name of a variant ("v128_c512", ...) or NULL. */
 const char* venom_spmm_variant_name(int variant);
 
 venom_status_t venom_get_info(const venom_handle_t* h, int64_t* R, int64_t* K, int* V, int* N, int* M);

@@ -4,22 +4,24 @@
 //   * the 2:4 inner pattern maps onto v_smfmac_f32_32x32x32_f16: A operand = 8 kept halfs per lane
 //     (row = lane%32, four groups), 16 index bits per lane (= four canonical nibbles), B operand =
 //     16 halfs per lane (column = lane%32, four groups x the 4 selected rows);
-//   * one workgroup owns a V x (64*NC) block of C (BS_r = V as in the paper, so every gathered row
-//     of B serves all V rows); a k-step is 8 groups = 32 gathered rows of B;
+//   * a workgroup owns V x (64*NC) blocks of C (BS_r = V as in the paper, so every gathered row of
+//     B serves all V rows); a k-step is 8 groups = 32 gathered rows of B;
 //   * the workgroup is split by role.  NC CONSUMER waves each own a 64-column strip: they only read
 //     LDS (transposing reads ds_read_b64_tr_b16 build the B operand, plain reads fetch the packed
 //     values and index words) and issue matrix instructions.  PRODUCER waves only move data, by
 //     direct-to-LDS loads: NPB of them gather the 32 rows of B of every k-step (XOR-swizzled per
 //     row so the transposing reads spread over the banks) into a 4-stage ring, three k-steps ahead;
 //     one more streams the packed A records into a deeper ring, NA-1 k-steps ahead, because that
-//     stream comes from HBM while B is L2-resident.  Loads retire in order per wave, so the two
-//     streams live in different waves.  The tail of each A record names the B rows of the k-step
-//     three steps later, so the gather addresses are on chip before they are needed.  A producer
-//     that has to queue behind the memory pipeline stalls alone; the matrix units keep running;
+//     stream comes from HBM while B is mostly L2-resident, and with them the row ids of B that the
+//     gather needs.  Loads retire in order per wave, so the streams live in different waves, and a
+//     producer that has to queue behind the memory pipeline stalls alone;
 //   * the loads are issued from inline assembly and retired with exact `s_waitcnt vmcnt(n)` counts;
 //     one s_barrier per k-step hands filled stages to the consumers and drained ones back;
-//   * the block index is remapped so that each XCD (one L2 each) walks a contiguous range of the
-//     column-tile-major work list and keeps its slab of B hot.
+//   * workgroups are persistent (one per compute unit): the k-steps of all tiles of a workgroup
+//     form one sequence, so the load pipeline runs on across tile boundaries while the consumers
+//     store their output;
+//   * each XCD (one L2 each) walks a contiguous range of the column-tile-major tile list and keeps
+//     its slab of B hot.
 #include <cstdio>
 #include <cstdlib>
 

@@ -42,6 +42,7 @@ CASES = [
     (64, 1400, 40, 32, 100),          # 2:100, G = 14: ragged last k-step
     (128, 336, 96, 64, 7),            # 2:7, G = 48
     (256, 64, 128, 128, 4),           # plain 2:4, G = 16
+    (192, 512, 136, 96, 8),           # V = 96 (three 32-row tiles), two block rows
 ]
 
 
