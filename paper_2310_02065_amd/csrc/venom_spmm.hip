@@ -48,6 +48,7 @@ struct SpmmParams {
   int per_xcd;             // ceil(nbr*nct / 8)
 #ifdef VENOM_ABLATE
   unsigned long long* trace;
+  int k_rows;              // rows of B: experiment builds clamp every gathered row id to it
 #endif
 };
 
@@ -55,7 +56,10 @@ struct SpmmParams {
 constexpr int kAbl = VENOM_ABLATE;   // experiment switches, fixed at compile time (never in the product library)
 #endif
 constexpr int kNumXcd = 8;
-constexpr int kStages = 4;           // B ring depth: three k-steps are in flight
+#ifndef VENOM_STAGES
+#define VENOM_STAGES 4
+#endif
+constexpr int kStages = VENOM_STAGES;           // B ring depth: three k-steps are in flight
 constexpr int kRidSlots = 16;        // row-id ring: 128 bytes per k-step
 
 // ---- direct-to-LDS loads and their retirement, outside the compiler's wait-count bookkeeping.
@@ -163,6 +167,9 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
   // tile, after which the consumers stage their output in the B stage they have just drained.
   const int G = tw.count * p.steps;
 
+#ifdef VENOM_PRODUCER_PRIO
+  if (wave >= NC) __builtin_amdgcn_s_setprio(VENOM_PRODUCER_PRIO);
+#endif
   if (wave == NC + NPB) {
     // ========================================================================= A producer
     // Streams, in one in-order queue: the packed records, PA steps ahead, and the row ids of B
@@ -211,12 +218,20 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
     int first_records = 0;
     for (int j = 0; j < RA && j < G; ++j) next_rowids();
     for (int j = 0; j < PA && j < G; ++j, ++first_records) next_record();
+#ifdef VENOM_ABLATE
+    if constexpr ((kAbl & (8 | 1024)) != 0) wait_loads_and_barrier<0>();   // no record loads to count behind
+    else
+#endif
     wait_units_and_barrier<NJ, PA>(first_records);  // the row ids (older than every record) have landed
     int c_s = 0;                                   // step inside the tile the consumers are on
     for (int g = 0; g < G; ++g) {
       // records g and g+1 have landed when at most the records after g+1 are pending; the row-id
       // loads in between only make the wait a little stricter
       const int left = G - 2 - g;
+#ifdef VENOM_ABLATE
+      if constexpr ((kAbl & (8 | 1024)) != 0) wait_loads_and_barrier<0>();
+      else
+#endif
       wait_units_and_barrier<NJ, PA - 2>(left < 0 ? 0 : left);
       // after the barrier everyone is done with record g-1: its slot takes record g+PA
       if (g + PA < G) next_record();
@@ -229,9 +244,9 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
     // B load q of this producer is load number pj + NPB*q of the k-step; it covers rows
     // (that number)*RPI .. +RPI-1; lane l writes 16-byte slot l%LPR of row l/LPR and fetches the
     // XOR-swizzled chunk of the gathered row.
-    // The row ids of a k-step sit in lane order in one register (lane l holds row l%32); the rows
-    // of one load are picked out with v_readlane and the byte offset of a lane is
-    // row * ldb_bytes + column offset, a 24-bit multiply-add (the host checks the ranges).
+    // The row ids of a k-step sit in lane order in one register (lane l holds row l%32); one
+    // 24-bit multiply turns them into byte offsets row * ldb_bytes (the host checks the ranges),
+    // the rows of one load are picked out with v_readlane, and a lane adds its column offset.
     int chunk_col[NBH];                            // first column of this lane's chunk inside the tile
 #pragma unroll
     for (int q = 0; q < NBH; ++q) {
@@ -260,17 +275,19 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
 #endif
       {
         const uint32_t sb = lds0 + b_slot * B_BYTES;
+        // byte offsets of all 32 rows at once (lane l: row l%32), then one v_readlane per row
+        const int rowoff = (int)__umul24((uint32_t)ridv, ldb24);
 #pragma unroll
         for (int q = 0; q < NBH; ++q) {
           if (q < NBL || hi) {
             const int rho0 = ((pj + NPB * q) % NI) * RPI;
-            int row = __builtin_amdgcn_readlane(ridv, rho0);
+            int off = __builtin_amdgcn_readlane(rowoff, rho0);
 #pragma unroll
             for (int k = 1; k < RPI; ++k) {
-              const int rk = __builtin_amdgcn_readlane(ridv, rho0 + k);
-              row = rowsel == k ? rk : row;
+              const int ok = __builtin_amdgcn_readlane(rowoff, rho0 + k);
+              off = rowsel == k ? ok : off;
             }
-            dma16(p.B, __umul24((uint32_t)row, ldb24) + ld_col[q], sb + (pj + NPB * q) * 1024);
+            dma16(p.B, (uint32_t)off + ld_col[q], sb + (pj + NPB * q) * 1024);
           }
         }
       }
@@ -281,7 +298,11 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
       }
     };
     auto rowids_of = [&](int g) {
-      return *reinterpret_cast<const int*>(smem + RIDRING + (g % kRidSlots) * (kStepRows * 4) + (lane & 31) * 4);
+      int r = *reinterpret_cast<const int*>(smem + RIDRING + (g % kRidSlots) * (kStepRows * 4) + (lane & 31) * 4);
+#ifdef VENOM_ABLATE
+      r = r < 0 ? 0 : (r >= p.k_rows ? p.k_rows - 1 : r);
+#endif
+      return r;
     };
     barrier_only();                                // the first row ids are on chip
     for (int j = 0; j < PB && j < G; ++j) issue(rowids_of(j));
@@ -503,6 +524,9 @@ venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, in
   p.C = C;
   p.ldb_bytes = ldb * 2; p.ldc = ldc; p.Ccols = Ccols; p.rec_bytes = L.rec_bytes;
   p.steps = (int)L.steps;
+#ifdef VENOM_ABLATE
+  p.k_rows = (int)h.K;
+#endif
 #ifdef VENOM_ABLATE
   static unsigned long long* trace_buf = nullptr;
   static int trace_calls = 0;
