@@ -46,6 +46,7 @@ struct SpmmParams {
   int steps;
   int nbr, nct;            // block rows, column tiles
   int per_xcd;             // ceil(nbr*nct / 8)
+  int stream_out;          // nonzero: non-temporal stores of C
 #ifdef VENOM_ABLATE
   unsigned long long* trace;
   int k_rows;              // rows of B: experiment builds clamp every gathered row id to it
@@ -89,6 +90,9 @@ __device__ __forceinline__ void wait_units_and_barrier(int k) {
   else if constexpr (MAXK > 0) wait_units_and_barrier<UNIT, MAXK - 1>(k);
 }
 __device__ __forceinline__ void barrier_only() { asm volatile("s_barrier" ::: "memory"); }
+// the same once every LDS read of this wave has returned (its reads of a stage must be over
+// before the barrier that hands the stage back)
+__device__ __forceinline__ void lgkm_drained_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 // 16-byte slot swizzle of gathered row rho inside its LDS row
 __device__ __forceinline__ int slot_swizzle(int rho) { return 4 * (rho & 3); }
@@ -130,7 +134,8 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
   constexpr int ARING = kStages * B_BYTES;         // LDS: [B ring][A ring][row-id ring]
   constexpr int RIDRING = ARING + NA * A_BYTES;
   constexpr int NJ = VT + 1;                       // A loads per k-step: VT value blocks + the tail
-  constexpr int PA = NA - 1;                       // k-steps the A stream runs ahead
+  constexpr int PA = NA - 2;                       // k-steps the A stream runs ahead (a record stays one step
+                                                   // longer than its k-step: the late consumers re-read it)
   constexpr int PB = kStages - 1;                  // k-steps the B stream runs ahead
   static_assert((kStages - 2) * NBH <= 63 && PA * NJ <= 63, "load counts fit the 6-bit counter");
   static_assert(NC * 4096 <= B_BYTES, "the output staging of all consumers fits one B stage");
@@ -167,9 +172,8 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
   // tile, after which the consumers stage their output in the B stage they have just drained.
   const int G = tw.count * p.steps;
 
-#ifdef VENOM_PRODUCER_PRIO
-  if (wave >= NC) __builtin_amdgcn_s_setprio(VENOM_PRODUCER_PRIO);
-#endif
+  // the producers' few instructions per k-step go ahead of the consumers' when both are ready
+  if (wave >= NC) __builtin_amdgcn_s_setprio(3);
   if (wave == NC + NPB) {
     // ========================================================================= A producer
     // Streams, in one in-order queue: the packed records, PA steps ahead, and the row ids of B
@@ -233,7 +237,7 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
       else
 #endif
       wait_units_and_barrier<NJ, PA - 2>(left < 0 ? 0 : left);
-      // after the barrier everyone is done with record g-1: its slot takes record g+PA
+      // after the barrier everyone is done with record g-2: its slot takes record g+PA
       if (g + PA < G) next_record();
       if (g + RA < G) next_rowids();
       if (++c_s == p.steps) { c_s = 0; barrier_only(); }
@@ -340,10 +344,51 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
           rd_off[tc][cb] = rho * ROW_BYTES + slot * 16 + (c8 & 1) * 8;
         }
     }
+    // One k-step of matrix work: operands bf (both 32-column B tiles) and ixw are in registers, the
+    // A operands stream from record `sa` through two alternating registers; av[0] may already hold
+    // tile row 0 (`have0`).
+    floatx16 acc[VT][2];
+    half16 bf[2];
+    uint2 ixw;                                     // 4 x 16 index bits
+    half8 av[2];
+    auto read_a = [&](const char* sa, int tr) {
+      return *reinterpret_cast<const half8*>(sa + tr * kTileValBytes + lane * 16);
+    };
+    auto read_b_ix = [&](const char* sb, const char* sa) {
+#pragma unroll
+      for (int tc = 0; tc < 2; ++tc)
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb) {
+          const short4v piece = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(short4v))(sb + rd_off[tc][cb]));
+          const half4 ph = __builtin_bit_cast(half4, piece);
+          bf[tc][4 * cb + 0] = ph[0]; bf[tc][4 * cb + 1] = ph[1]; bf[tc][4 * cb + 2] = ph[2]; bf[tc][4 * cb + 3] = ph[3];
+        }
+      ixw = *reinterpret_cast<const uint2*>(sa + T_OFF + lane * 8);
+    };
+    auto multiply = [&](const char* sa, bool have0) {
+      if (!have0) av[0] = read_a(sa, 0);
+      if (VT > 1) av[1] = read_a(sa, 1);
+#pragma unroll
+      for (int tr = 0; tr < VT; ++tr) {
+        const int ix = (int)((tr >> 1) ? ixw.y : ixw.x);
+#pragma unroll
+        for (int tc = 0; tc < 2; ++tc) {
+          if (tr & 1) acc[tr][tc] = smfmac<1>(av[tr & 1], bf[tc], acc[tr][tc], ix);
+          else acc[tr][tc] = smfmac<0>(av[tr & 1], bf[tc], acc[tr][tc], ix);
+        }
+        if (tr + 2 < VT) av[tr & 1] = read_a(sa, tr + 2);
+      }
+    };
+    // The two consumer waves that share a SIMD work half a k-step apart: the EARLY one reads its
+    // operands right after the barrier and multiplies when they arrive; the LATE one first
+    // multiplies with the operands it fetched during the previous k-step, then fetches this one's.
+    // So one wave's LDS latency hides behind the other's matrix instructions.  Every LDS read of a
+    // stage still happens inside that stage's k-step; the late wave re-reads A tile rows of the
+    // previous record, which is why the A ring is refilled one step later than it is consumed.
+    const bool late = (wave / (NC / 2)) & 1;
     int b_slot = 0, a_slot = 0;
     barrier_only();                                // (the producers' start-up barrier)
     for (int t = 0; t < tw.count; ++t) {
-      floatx16 acc[VT][2];
 #pragma unroll
       for (int tr = 0; tr < VT; ++tr)
 #pragma unroll
@@ -352,52 +397,37 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
           for (int v = 0; v < 16; ++v) acc[tr][tc][v] = 0.f;
 
       const char* sb = smem;
-      for (int s = 0; s < p.steps; ++s) {
-        barrier_only();                            // this k-step is complete in LDS
+      const char* sa = smem;
+      auto advance = [&]() {
         sb = smem + b_slot * B_BYTES;
-        const char* sa = smem + ARING + a_slot * A_BYTES;
+        sa = smem + ARING + a_slot * A_BYTES;
         b_slot = (b_slot + 1) % kStages;
         a_slot = a_slot + 1 == NA ? 0 : a_slot + 1;
-#ifdef VENOM_ABLATE
-        if (kAbl & 4) continue;
-        constexpr bool no_lds = kAbl & 64;         // matrix instructions on whatever the registers hold
-#else
-        constexpr bool no_lds = false;
-#endif
-        half16 bf[2];
-        if (no_lds) asm volatile("" : "=v"(bf[0]), "=v"(bf[1]));
-        else
-#pragma unroll
-        for (int tc = 0; tc < 2; ++tc)
-#pragma unroll
-          for (int cb = 0; cb < 4; ++cb) {
-            const short4v piece = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(short4v))(sb + rd_off[tc][cb]));
-            const half4 ph = __builtin_bit_cast(half4, piece);
-            bf[tc][4 * cb + 0] = ph[0]; bf[tc][4 * cb + 1] = ph[1]; bf[tc][4 * cb + 2] = ph[2]; bf[tc][4 * cb + 3] = ph[3];
-          }
-        uint2 ixw;                                 // 4 x 16 index bits
-        if (no_lds) asm volatile("" : "=v"(ixw));
-        else ixw = *reinterpret_cast<const uint2*>(sa + T_OFF + lane * 8);
-#pragma unroll
-        for (int tr = 0; tr < VT; ++tr) {
-          half8 av;
-          if (no_lds) asm volatile("" : "=v"(av));
-          else av = *reinterpret_cast<const half8*>(sa + tr * kTileValBytes + lane * 16);
-          const int ix = (int)((tr >> 1) ? ixw.y : ixw.x);
-#ifdef VENOM_ABLATE
-          if (kAbl & 32) {                         // LDS reads only
-            asm volatile("" ::"v"(av), "v"(bf[0]), "v"(bf[1]), "v"(ix));
-            continue;
-          }
-#endif
-#pragma unroll
-          for (int tc = 0; tc < 2; ++tc) {
-            if (tr & 1) acc[tr][tc] = smfmac<1>(av, bf[tc], acc[tr][tc], ix);
-            else acc[tr][tc] = smfmac<0>(av, bf[tc], acc[tr][tc], ix);
-          }
+      };
+      if (!late) {
+        for (int s = 0; s < p.steps; ++s) {
+          barrier_only();                          // this k-step is complete in LDS
+          advance();
+          read_b_ix(sb, sa);
+          multiply(sa, false);
         }
+        barrier_only();                            // every consumer has drained the last B stage
+      } else {
+        lgkm_drained_barrier();
+        advance();
+        read_b_ix(sb, sa);
+        av[0] = read_a(sa, 0);
+        for (int s = 1; s < p.steps; ++s) {
+          const char* sa_prev = sa;
+          lgkm_drained_barrier();                  // this k-step is complete; my reads of the last one are done
+          advance();
+          multiply(sa_prev, true);
+          read_b_ix(sb, sa);
+          av[0] = read_a(sa, 0);
+        }
+        lgkm_drained_barrier();                    // every consumer has drained the last B stage
+        multiply(sa, true);
       }
-      barrier_only();                              // every consumer has drained the last B stage
 
       // ---- stage 3: registers -> (LDS) -> global.  Accumulator element v of a 32x32 tile sits
       // at row 8*(v/4) + 4*(lane/32) + v%4, column lane%32.
@@ -449,7 +479,15 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
           for (int i = 0; i < 4; ++i) {
             const int r = i * 8 + rsub;
             const uint4 val = *reinterpret_cast<const uint4*>(stg + r * 128 + ((chunk ^ (4 * ((r >> 2) & 1))) * 16));
-            if (col < p.Ccols) *reinterpret_cast<uint4*>(Ch + (row0 + tr * 32 + r) * p.ldc + col) = val;
+            if (col < p.Ccols) {
+              typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+              u32x4* dst = reinterpret_cast<u32x4*>(Ch + (row0 + tr * 32 + r) * p.ldc + col);
+              const u32x4 v4 = {val.x, val.y, val.z, val.w};
+              // streaming stores keep C out of the L2 that holds the slab of B; they drain more
+              // slowly, so the host asks for them only where the output is a small share of the traffic
+              if (p.stream_out) __builtin_nontemporal_store(v4, dst);
+              else *dst = v4;
+            }
           }
         }
       }
@@ -524,6 +562,7 @@ venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, in
   p.C = C;
   p.ldb_bytes = ldb * 2; p.ldc = ldc; p.Ccols = Ccols; p.rec_bytes = L.rec_bytes;
   p.steps = (int)L.steps;
+  p.stream_out = L.steps >= 32;   // measured: +3 % at 48 k-steps per tile, -20 % at 8
 #ifdef VENOM_ABLATE
   p.k_rows = (int)h.K;
 #endif
