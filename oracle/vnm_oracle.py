@@ -24,7 +24,9 @@ padding when fewer than 4 columns / 2 entries are used, word packing of the 2-bi
 
 Pins (tests/test_oracle_*.py): hand-derived golden arrays, compress->decompress round trip,
 format invariants, brute-force triple loop on the dense masked matrix, B = identity, all-ones
-closed form 2K/M, the M=4 special case against a plain sub-matrix product.
+closed form 2K/M, the M=4 special case against a plain sub-matrix product; for the epilogue
+(tests/test_oracle_epilogue.py) tabulated values of the normal distribution, GELU's identities,
+minimum and slope bound, and the tanh form's known distance from the definition.
 """
 from __future__ import annotations
 
@@ -227,3 +229,46 @@ def accept(C_test: np.ndarray, C_star: np.ndarray, E: np.ndarray, elem_tol=1e-2,
     den = float(np.sqrt(np.sum(C_star * C_star)))
     fro = num / den if den > 0 else (0.0 if num == 0 else np.inf)
     return (worst <= 0.0) and (fro <= fro_tol), {"max_excess": worst, "rel_fro": fro}
+
+
+# ---------------------------------------------------------------------------------------------
+# Fused epilogue of the product: the paper's call is spmm(values, columns, metadata, input, bias)
+# (section 7.2, "Case study: sparse LLMs": the sparse layer replaces a linear layer, so the bias
+# of the layer is added to every output row = output feature).  An optional GELU follows, in its
+# definition x * Phi(x) or in the tanh form transformer code bases use.
+GELU_LIPSCHITZ = 1.13          # sup |gelu'(x)| = 1.1289 (at x = sqrt(2)): GELU stretches an error by at most this
+
+
+def gelu_erf(x: np.ndarray) -> np.ndarray:
+    """GELU(x) = x * Phi(x) = x/2 * (1 + erf(x / sqrt 2)), the definition, in fp64."""
+    import math
+    erf = np.vectorize(math.erf, otypes=[np.float64])
+    x = np.asarray(x, dtype=np.float64)
+    return 0.5 * x * (1.0 + erf(x / math.sqrt(2.0)))
+
+
+def gelu_tanh(x: np.ndarray) -> np.ndarray:
+    """The tanh form: x/2 * (1 + tanh(sqrt(2/pi) * (x + 0.044715 x^3))), in fp64."""
+    x = np.asarray(x, dtype=np.float64)
+    return 0.5 * x * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (x + 0.044715 * x * x * x)))
+
+
+ACTIVATIONS = {"none": None, "gelu": gelu_erf, "gelu_tanh": gelu_tanh}
+
+
+def epilogue_fp64(C_star: np.ndarray, E: np.ndarray, bias_bits, activation: str = "none"):
+    """Y = act(C* + bias[:, None]).  Returns (Y, E_y): E_y bounds how far Y may move when the
+    pre-activation moves by the product's own bound: the magnitude sum grows by |bias| (the add
+    is one more rounded term) and an activation stretches it by its Lipschitz constant."""
+    Z = np.array(C_star, dtype=np.float64, copy=True)
+    Ez = np.array(E, dtype=np.float64, copy=True)
+    if bias_bits is not None:
+        b = f16_bits_to_f64(np.asarray(bias_bits).reshape(-1))
+        if b.shape[0] != Z.shape[0]:
+            raise ValueError("bias needs one entry per row of C")
+        Z += b[:, None]
+        Ez += np.abs(b)[:, None]
+    act = ACTIVATIONS[activation]
+    if act is None:
+        return Z, Ez
+    return act(Z), GELU_LIPSCHITZ * Ez
