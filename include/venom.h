@@ -108,6 +108,16 @@ venom_status_t venom_spmm(const venom_handle_t* h, const void* B_f16_dev, int64_
  * VENOM_ERR_UNSUPPORTED.  venom_spmm_variant_count() variants exist, numbered from 0. */
 venom_status_t venom_spmm_variant(const venom_handle_t* h, const void* B_f16_dev, int64_t ldb, int64_t C_cols,
                                   void* C_dev, int64_t ldc, int c_dtype, int variant, void* stream);
+/* The product with the layer's epilogue fused into the output stage (the paper's library call
+ * takes the bias of the linear layer it replaces: section 7.2, the spmm(values, columns,
+ * metadata, input, bias) call): C = act(A . B + bias), bias one fp16 entry per ROW of C (row =
+ * output feature), added in fp32 before the single rounding; NULL = no bias.  `activation` is a
+ * venom_activation_t: GELU by its definition x * Phi(x), or its tanh form.  bias must be 8-byte
+ * aligned.  Everything else as venom_spmm_variant (variant < 0 = automatic). */
+typedef enum { VENOM_ACT_NONE = 0, VENOM_ACT_GELU = 1, VENOM_ACT_GELU_TANH = 2 } venom_activation_t;
+venom_status_t venom_spmm_bias_act(const venom_handle_t* h, const void* B_f16_dev, int64_t ldb, int64_t C_cols,
+                                   const void* bias_f16_dev, int activation, void* C_dev, int64_t ldc, int c_dtype,
+                                   int variant, void* stream);
 int venom_spmm_variant_count(void);
 /* Name of a variant ("v128_c512", ...) or NULL. */
 const char* venom_spmm_variant_name(int variant);

@@ -23,7 +23,7 @@ STATUS_NAMES = {
 
 # every symbol include/venom.h declares
 EXPORTS = ("venom_workspace_bytes", "venom_compress", "venom_import", "venom_export", "venom_decompress",
-           "venom_spmm", "venom_spmm_variant", "venom_spmm_variant_count", "venom_spmm_variant_name",
+           "venom_spmm", "venom_spmm_variant", "venom_spmm_bias_act", "venom_spmm_variant_count", "venom_spmm_variant_name",
            "venom_get_info", "venom_destroy", "venom_status_string")
 
 
@@ -61,6 +61,8 @@ def lib() -> ctypes.CDLL:
     L.venom_decompress.argtypes = [c_void_p, c_void_p, c_int64, c_void_p]
     L.venom_spmm.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_void_p, c_int64, c_int, c_void_p]
     L.venom_spmm_variant.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_void_p, c_int64, c_int, c_int, c_void_p]
+    L.venom_spmm_bias_act.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_void_p, c_int, c_void_p, c_int64, c_int,
+                                      c_int, c_void_p]
     L.venom_spmm_variant_count.argtypes = []
     L.venom_spmm_variant_name.argtypes = [c_int]
     L.venom_spmm_variant_name.restype = c_char_p
@@ -71,7 +73,7 @@ def lib() -> ctypes.CDLL:
     L.venom_status_string.argtypes = [c_int]
     L.venom_status_string.restype = c_char_p
     for name in ("venom_workspace_bytes", "venom_compress", "venom_import", "venom_export", "venom_decompress",
-                 "venom_spmm", "venom_spmm_variant", "venom_spmm_variant_count", "venom_get_info"):
+                 "venom_spmm", "venom_spmm_variant", "venom_spmm_bias_act", "venom_spmm_variant_count", "venom_get_info"):
         getattr(L, name).restype = c_int
     _lib = L
     return L
@@ -184,8 +186,12 @@ def venom_decompress(h: Handle, out=None, stream=None):
     return out
 
 
-def venom_spmm(h: Handle, B, out=None, out_dtype=None, variant=-1, stream=None):
-    """C = A . B.  B: K x C float16 CUDA tensor (unit column stride); returns/fills C (R x C)."""
+ACTIVATIONS = {"none": 0, "gelu": 1, "gelu_tanh": 2}
+
+
+def venom_spmm(h: Handle, B, out=None, out_dtype=None, variant=-1, stream=None, bias=None, activation="none"):
+    """C = act(A . B + bias[:, None]).  B: K x C float16 CUDA tensor (unit column stride);
+    bias: float16 CUDA vector of R entries or None; returns/fills C (R x C)."""
     import torch
     assert B.is_cuda and B.dtype == torch.float16 and B.dim() == 2 and B.stride(1) == 1
     Ccols = B.shape[1]
@@ -195,7 +201,11 @@ def venom_spmm(h: Handle, B, out=None, out_dtype=None, variant=-1, stream=None):
     c_dtype = 1 if out.dtype == torch.float32 else 0
     ldb = B.stride(0) if B.shape[0] > 1 else max(Ccols, B.stride(0))
     ldc = out.stride(0) if out.shape[0] > 1 else max(Ccols, out.stride(0))
-    st = lib().venom_spmm_variant(h.ptr, _ptr(B), ldb, Ccols, _ptr(out), ldc, c_dtype, variant, _stream_ptr(stream))
+    if bias is not None:
+        assert bias.is_cuda and bias.dtype == torch.float16 and bias.dim() == 1 and bias.shape[0] == h.R
+        assert bias.stride(0) == 1
+    st = lib().venom_spmm_bias_act(h.ptr, _ptr(B), ldb, Ccols, _ptr(bias), ACTIVATIONS[activation], _ptr(out), ldc,
+                                   c_dtype, variant, _stream_ptr(stream))
     if st != VENOM_OK:
         raise VenomError(st, "venom_spmm")
     return out

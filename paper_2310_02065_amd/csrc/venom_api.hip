@@ -137,9 +137,13 @@ venom_status_t venom_decompress(const venom_handle_t* h, void* A_f16_dev, int64_
   return e == hipSuccess ? VENOM_OK : VENOM_ERR_HIP;
 }
 
-venom_status_t venom_spmm_variant(const venom_handle_t* h, const void* B_f16_dev, int64_t ldb, int64_t C_cols,
-                                  void* C_dev, int64_t ldc, int c_dtype, int variant, void* stream) {
+venom_status_t venom_spmm_bias_act(const venom_handle_t* h, const void* B_f16_dev, int64_t ldb, int64_t C_cols,
+                                   const void* bias_f16_dev, int activation, void* C_dev, int64_t ldc, int c_dtype,
+                                   int variant, void* stream) {
   if (!h) return VENOM_ERR_INVALID_ARG;
+  if (activation != VENOM_ACT_NONE && activation != VENOM_ACT_GELU && activation != VENOM_ACT_GELU_TANH)
+    return VENOM_ERR_INVALID_ARG;
+  if (bias_f16_dev && !aligned(bias_f16_dev, 8)) return VENOM_ERR_UNSUPPORTED;
   if (c_dtype != 0 && c_dtype != 1) return VENOM_ERR_INVALID_ARG;
   if (C_cols < 0) return VENOM_ERR_INVALID_ARG;
   if (C_cols < 1) return VENOM_ERR_SHAPE;
@@ -149,7 +153,13 @@ venom_status_t venom_spmm_variant(const venom_handle_t* h, const void* B_f16_dev
   const size_t esz = c_dtype == 1 ? 4 : 2;
   if (!aligned(B_f16_dev, 16) || !aligned(C_dev, 16) || (ldb * 2) % 16 != 0 || (ldc * esz) % 16 != 0)
     return VENOM_ERR_UNSUPPORTED;
-  return venom::launch_spmm(*h, B_f16_dev, ldb, C_cols, C_dev, ldc, c_dtype, variant, static_cast<hipStream_t>(stream));
+  return venom::launch_spmm(*h, B_f16_dev, ldb, C_cols, bias_f16_dev, activation, C_dev, ldc, c_dtype, variant,
+                            static_cast<hipStream_t>(stream));
+}
+
+venom_status_t venom_spmm_variant(const venom_handle_t* h, const void* B_f16_dev, int64_t ldb, int64_t C_cols,
+                                  void* C_dev, int64_t ldc, int c_dtype, int variant, void* stream) {
+  return venom_spmm_bias_act(h, B_f16_dev, ldb, C_cols, nullptr, VENOM_ACT_NONE, C_dev, ldc, c_dtype, variant, stream);
 }
 
 venom_status_t venom_spmm(const venom_handle_t* h, const void* B_f16_dev, int64_t ldb, int64_t C_cols, void* C_dev,

@@ -57,7 +57,7 @@ hipError_t launch_decompress(const venom_handle& h, uint16_t* A, int64_t lda, hi
 int spmm_variant_count();
 const char* spmm_variant_name(int v);
 // returns VENOM_OK / VENOM_ERR_UNSUPPORTED / VENOM_ERR_HIP
-venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, int64_t Ccols, void* C, int64_t ldc,
-                           int c_dtype, int variant, hipStream_t st);
+venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, int64_t Ccols, const void* bias, int act,
+                           void* C, int64_t ldc, int c_dtype, int variant, hipStream_t st);
 
 }  // namespace venom

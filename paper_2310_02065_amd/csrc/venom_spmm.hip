@@ -47,6 +47,8 @@ struct SpmmParams {
   int nbr, nct;            // block rows, column tiles
   int per_xcd;             // ceil(nbr*nct / 8)
   int stream_out;          // nonzero: non-temporal stores of C
+  const _Float16* bias;    // one entry per row of C, or null
+  int act;                 // venom_activation_t
 #ifdef VENOM_ABLATE
   unsigned long long* trace;
   int k_rows;              // rows of B: experiment builds clamp every gathered row id to it
@@ -97,6 +99,28 @@ __device__ __forceinline__ void lgkm_drained_barrier() { asm volatile("s_waitcnt
 // 16-byte slot swizzle of gathered row rho inside its LDS row
 __device__ __forceinline__ int slot_swizzle(int rho) { return 4 * (rho & 3); }
 
+// GELU(x) = x * Phi(x) = x/2 * (1 + erf(x / sqrt 2)).  erf by the rational-times-Gaussian formula
+// 7.1.26 of Abramowitz & Stegun (absolute error below 1.5e-7, fp32 noise level), a dozen
+// instructions with the hardware exp2 and reciprocal: the output stage evaluates it 128 times per
+// lane, fully unrolled, so a library erff would cost more code than the rest of the kernel.
+__device__ __forceinline__ float gelu_by_definition(float x) {
+  const float z = fabsf(x) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.f));
+  float poly = fmaf(1.061405429f, t, -1.453152027f);
+  poly = fmaf(poly, t, 1.421413741f);
+  poly = fmaf(poly, t, -0.284496736f);
+  poly = fmaf(poly, t, 0.254829592f);
+  const float tail = poly * t * __builtin_amdgcn_exp2f(-1.4426950408889634f * z * z);   // 1 - erf(z)
+  const float phi = x < 0.f ? 0.5f * tail : 1.f - 0.5f * tail;                           // Phi(x)
+  return x * phi;
+}
+// The tanh form x/2 * (1 + tanh u), u = sqrt(2/pi) (x + 0.044715 x^3), written as x / (1 + e^(-2u)).
+__device__ __forceinline__ float gelu_tanh_form(float x) {
+  const float u = 0.79788456080286536f * x * fmaf(0.044715f * x, x, 1.f);
+  const float e = __builtin_amdgcn_exp2f(-2.f * 1.4426950408889634f * u);
+  return x * __builtin_amdgcn_rcpf(1.f + e);
+}
+
 template <int ABID>
 __device__ __forceinline__ floatx16 smfmac(half8 a, half16 b, floatx16 c, int idx) {
   return __builtin_amdgcn_smfmac_f32_32x32x32_f16(a, b, c, idx, 0, ABID);
@@ -117,7 +141,7 @@ struct TileWalk {
   }
 };
 
-template <int VT, int NC, int NPB, int NA, bool OUT_F32>
+template <int VT, int NC, int NPB, int NA, bool OUT_F32, bool EPI>
 __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams p) {
   static_assert(NC == 2 || NC == 4 || NC == 8, "consumer waves per workgroup");
   static_assert(VT >= 1 && VT <= kMaxTiles, "32-row tiles per block row");
@@ -438,10 +462,39 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
       tw.locate(p, t, ct, br);
       const int64_t row0 = (int64_t)br * VT * 32;
       const int64_t col0 = (int64_t)ct * BSC + wave * 64;
+      // fused epilogue (the layer's bias, one per output row, then the activation), in fp32 on
+      // the accumulators, one 32-row tile at a time right before it is stored: a lane holds rows
+      // 8j + 4*(lane/32) + 0..3 of the tile
+      auto finish = [&](int tr) {
+        if constexpr (!EPI) return;                // the plain product compiles without any of this
+        if (p.bias) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const half4 b4 = *reinterpret_cast<const half4*>(p.bias + row0 + tr * 32 + 8 * j + 4 * (lane >> 5));
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              acc[tr][0][4 * j + i] += (float)b4[i];
+              acc[tr][1][4 * j + i] += (float)b4[i];
+            }
+          }
+        }
+        if (p.act == VENOM_ACT_GELU) {
+#pragma unroll
+          for (int tc = 0; tc < 2; ++tc)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[tr][tc][v] = gelu_by_definition(acc[tr][tc][v]);
+        } else if (p.act == VENOM_ACT_GELU_TANH) {
+#pragma unroll
+          for (int tc = 0; tc < 2; ++tc)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[tr][tc][v] = gelu_tanh_form(acc[tr][tc][v]);
+        }
+      };
       if constexpr (OUT_F32) {
         float* Cf = reinterpret_cast<float*>(p.C);
 #pragma unroll
-        for (int tr = 0; tr < VT; ++tr)
+        for (int tr = 0; tr < VT; ++tr) {
+          finish(tr);
 #pragma unroll
           for (int tc = 0; tc < 2; ++tc) {
             const int64_t col = col0 + tc * 32 + (lane & 31);
@@ -453,6 +506,8 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
               }
             }
           }
+          __builtin_amdgcn_sched_barrier(0);
+        }
       } else {
         // One 32 x 64 tile row at a time through this wave's 4 KB of the drained stage (the
         // producers refill that stage only after the next barrier).  A staged row is 128 bytes;
@@ -464,6 +519,7 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
         const int64_t col = col0 + chunk * 8;
 #pragma unroll
         for (int tr = 0; tr < VT; ++tr) {
+          finish(tr);
 #pragma unroll
           for (int tc = 0; tc < 2; ++tc) {
             const int c = tc * 32 + (lane & 31);
@@ -489,6 +545,7 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
               else *dst = v4;
             }
           }
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
     }
@@ -508,8 +565,7 @@ struct Variant {
   int bsc;     // columns per workgroup
   int threads;
   int lds;     // dynamic LDS bytes
-  void (*f16)(SpmmParams);
-  void (*f32)(SpmmParams);
+  void (*fn[2][2])(SpmmParams);   // [fp32 output][fused bias/activation]
 };
 
 template <int VT, int NC, int NA>
@@ -519,7 +575,8 @@ constexpr int lds_bytes() {   // B ring, A ring, row-id ring (the output staging
 
 #define VARIANT(NAME, VT, NC, NPB, NA)                                                         \
   { NAME, (VT) * 32, 64 * (NC), 64 * ((NC) + (NPB) + 1), lds_bytes<VT, NC, NA>(),                \
-    spmm_kernel<VT, NC, NPB, NA, false>, spmm_kernel<VT, NC, NPB, NA, true> }
+    { { spmm_kernel<VT, NC, NPB, NA, false, false>, spmm_kernel<VT, NC, NPB, NA, false, true> },       \
+      { spmm_kernel<VT, NC, NPB, NA, true, false>, spmm_kernel<VT, NC, NPB, NA, true, true> } } }
 
 static const Variant kVariants[] = {
     VARIANT("v128_c512", 4, 8, 3, 6), VARIANT("v128_c256", 4, 4, 2, 9), VARIANT("v128_c128", 4, 2, 1, 10),
@@ -547,8 +604,8 @@ static int pick_variant(int V, int64_t Ccols, int64_t nbr) {
   return best;
 }
 
-venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, int64_t Ccols, void* C, int64_t ldc,
-                           int c_dtype, int variant, hipStream_t st) {
+venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, int64_t Ccols, const void* bias, int act,
+                           void* C, int64_t ldc, int c_dtype, int variant, hipStream_t st) {
   const Layout& L = h.lay;
   if (!L.packed) return VENOM_ERR_UNSUPPORTED;
   if (L.R == 0 || Ccols == 0) return VENOM_OK;
@@ -562,6 +619,8 @@ venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, in
   p.C = C;
   p.ldb_bytes = ldb * 2; p.ldc = ldc; p.Ccols = Ccols; p.rec_bytes = L.rec_bytes;
   p.steps = (int)L.steps;
+  p.bias = reinterpret_cast<const _Float16*>(bias);
+  p.act = act;
   p.stream_out = L.steps >= 32;   // measured: +3 % at 48 k-steps per tile, -20 % at 8
 #ifdef VENOM_ABLATE
   p.k_rows = (int)h.K;
@@ -594,15 +653,16 @@ venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, in
   const unsigned grid = (unsigned)(wg_per_xcd * kNumXcd);
   // a workgroup numbers the k-steps of all its tiles with one 32-bit counter
   if ((p.per_xcd + wg_per_xcd - 1) / wg_per_xcd * L.steps >= ((int64_t)1 << 30)) return VENOM_ERR_UNSUPPORTED;
-  auto fn = c_dtype == 1 ? var.f32 : var.f16;
+  const int epi = (bias != nullptr || act != VENOM_ACT_NONE) ? 1 : 0;
+  auto fn = var.fn[c_dtype == 1 ? 1 : 0][epi];
   if (var.lds > 64 * 1024) {
     // opting in to more than 64 KB of dynamic LDS is a per-function attribute (set once per device)
-    static bool opted_in[kNumVariants][2][16] = {};
-    if (dev < 0 || dev >= 16 || !opted_in[variant][c_dtype][dev]) {
+    static bool opted_in[kNumVariants][4][16] = {};
+    if (dev < 0 || dev >= 16 || !opted_in[variant][2 * c_dtype + epi][dev]) {
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
                               var.lds) != hipSuccess)
         return VENOM_ERR_HIP;
-      if (dev >= 0 && dev < 16) opted_in[variant][c_dtype][dev] = true;
+      if (dev >= 0 && dev < 16) opted_in[variant][2 * c_dtype + epi][dev] = true;
     }
   }
   const int launch_lds = var.lds;

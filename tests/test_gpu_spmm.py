@@ -123,3 +123,55 @@ def test_argument_errors():
     with pytest.raises(binding.VenomError) as e:      # V not a multiple of 32
         binding.venom_spmm(h8, torch.zeros((48, 8), dtype=torch.float16, device=DEV))
     assert e.value.status == binding.VENOM_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("activation", ["none", "gelu", "gelu_tanh"])
+@pytest.mark.parametrize("out_dtype", [torch.float16, torch.float32])
+@pytest.mark.parametrize("R,K,C,V,M", [(256, 384, 264, 128, 8), (192, 896, 136, 64, 16), (128, 720, 72, 32, 10)])
+def test_fused_bias_and_activation(R, K, C, V, M, out_dtype, activation):
+    A, mask, B = inputs.gen_problem(R, K, C, V, M, 1.0, seed=900 + R + M)
+    rng = np.random.default_rng(77 + R)
+    bias = rng.standard_normal(R).astype(np.float16)
+    h = compress_dev(A, mask, V, M)
+    ov, oc, om = o.compress(A, mask, V, M)
+    Cs, E = o.spmm_fp64(ov, oc, om, R, K, V, M, B)
+    for with_bias in (True, False):
+        if not with_bias and activation == "none":
+            continue                      # the plain product is covered above
+        Ys, Ey = o.epilogue_fp64(Cs, E, bias.view(np.uint16) if with_bias else None, activation)
+        bias_d = torch.from_numpy(bias).to(DEV) if with_bias else None
+        for v in variants_for(V):
+            out = binding.venom_spmm(h, to_dev_f16(B), out_dtype=out_dtype, variant=v, bias=bias_d,
+                                     activation=activation)
+            ok, info = o.accept(out.float().cpu().numpy().astype(np.float64), Ys, Ey)
+            assert ok, (binding.venom_spmm_variants()[v], with_bias, info)
+
+
+def test_zero_product_returns_activation_of_bias_exactly_in_fp32():
+    R, K, C, V, M = 128, 256, 64, 128, 8
+    A, mask, _ = inputs.gen_problem(R, K, C, V, M, 1.0, seed=11)
+    h = compress_dev(A, mask, V, M)
+    B0 = torch.zeros((K, C), dtype=torch.float16, device=DEV)
+    bias = np.linspace(-3, 3, R).astype(np.float16)
+    out = binding.venom_spmm(h, B0, out_dtype=torch.float32, bias=torch.from_numpy(bias).to(DEV))
+    assert np.array_equal(out.cpu().numpy(), np.repeat(bias.astype(np.float32)[:, None], C, axis=1))
+    outg = binding.venom_spmm(h, B0, out_dtype=torch.float32, bias=torch.from_numpy(bias).to(DEV), activation="gelu")
+    ref = o.gelu_erf(bias.astype(np.float64))
+    assert np.abs(outg.cpu().numpy()[:, 0] - ref).max() < 2e-6
+    assert (outg.cpu().numpy() == outg.cpu().numpy()[:, :1]).all()
+
+
+def test_epilogue_argument_errors():
+    R, K, C, V, M = 64, 64, 64, 32, 8
+    A, mask, B = inputs.gen_problem(R, K, C, V, M, 1.0, seed=5)
+    h = compress_dev(A, mask, V, M)
+    out = torch.empty((R, C), dtype=torch.float16, device=DEV)
+    L = binding.lib()
+    import ctypes
+    st = L.venom_spmm_bias_act(h.ptr, ctypes.c_void_p(to_dev_f16(B).data_ptr()), C, C, None, 7,
+                               ctypes.c_void_p(out.data_ptr()), C, 0, -1, None)
+    assert st == binding.VENOM_ERR_INVALID_ARG
+    bias = torch.zeros(R + 8, dtype=torch.float16, device=DEV)
+    st = L.venom_spmm_bias_act(h.ptr, ctypes.c_void_p(to_dev_f16(B).data_ptr()), C, C,
+                               ctypes.c_void_p(bias.data_ptr() + 2), 0, ctypes.c_void_p(out.data_ptr()), C, 0, -1, None)
+    assert st == binding.VENOM_ERR_UNSUPPORTED
