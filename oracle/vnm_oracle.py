@@ -272,3 +272,46 @@ def epilogue_fp64(C_star: np.ndarray, E: np.ndarray, bias_bits, activation: str 
     if act is None:
         return Z, Ez
     return act(Z), GELU_LIPSCHITZ * Ez
+
+
+# ---------------------------------------------------------------------------------------------
+# Magnitude pruning to V:N:M (section 3, the two pruning stages; section 5, the energy metric).
+# The paper does not say how "most significant" is measured for a column of a block; the reading
+# taken is the column's L1 mass over the V rows (the sum the energy metric itself is made of), and
+# |w| for the per-row stage.  Ties go to the smaller index.  Masses are EXACT: every fp16 is an
+# integer multiple of 2^-24, so magnitudes are summed as integers and no rounding order exists.
+MAG_NONFINITE = 1 << 40        # Inf / NaN count as more than any finite fp16 (65504 = 2047 * 2^29 units)
+
+
+def magnitude_units(bits: np.ndarray) -> np.ndarray:
+    """|w| of fp16 bit patterns in units of 2^-24, as int64 (exact)."""
+    b = np.asarray(bits).astype(np.int64)
+    e = (b >> 10) & 31
+    f = b & 1023
+    normal = (1024 + f) << np.maximum(e - 1, 0)
+    return np.where(e == 0, f, np.where(e == 31, MAG_NONFINITE, normal)).astype(np.int64)
+
+
+def prune(A_bits: np.ndarray, V: int, M: int):
+    """One-shot magnitude pruning: per V x M block keep the 4 columns of largest L1 mass, then in
+    every row the 2 largest |w| among those 4.  Returns (mask uint8 R x K, kept_mass, total_mass)
+    with the masses as Python integers in units of 2^-24 (energy = kept_mass / total_mass)."""
+    A_bits = np.asarray(A_bits)
+    R, K = A_bits.shape
+    Rb, G = _dims(R, K, V, M)
+    mag = magnitude_units(A_bits)
+    mask = np.zeros((R, K), dtype=np.uint8)
+    kept = 0
+    for b in range(Rb):
+        for g in range(G):
+            blk = mag[b * V:(b + 1) * V, g * M:(g + 1) * M]
+            mass = blk.sum(axis=0)                                   # exact integers
+            order = sorted(range(M), key=lambda c: (-int(mass[c]), c))
+            cols = sorted(order[:SEL_COLS])
+            for v in range(V):
+                row = [(-int(blk[v, c]), p) for p, c in enumerate(cols)]
+                for _, p in sorted(row)[:N_KEEP]:
+                    mask[b * V + v, g * M + cols[p]] = 1
+                    kept += int(blk[v, cols[p]])
+    total = int(sum(int(x) for x in mag.sum(axis=1)))
+    return mask, kept, total
