@@ -88,10 +88,9 @@ def test_plausible_wrong_rules_give_different_masks_here():
     assert kept == 12 << 24 and total == 29 << 24
     # per-row top-2 over all M columns (skipping the block stage) would keep the 8 in column 0
     C = f16([[8, 1, 1, 1, 1, 0],
-             [0, 2, 2, 2, 2, 0],
-             [0, 2, 2, 2, 2, 0],
-             [0, 2, 2, 2, 2, 0],
-             [0, 2, 2, 2, 2, 0]] [:4])
+             [0, 3, 3, 3, 3, 0],
+             [0, 3, 3, 3, 3, 0],
+             [0, 3, 3, 3, 3, 0]])
     m, _, _ = o.prune(C, 4, 6)
     assert m[0, 0] == 0 and m[0].sum() == 2
     # signs do not matter, only magnitudes
