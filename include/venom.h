@@ -87,6 +87,18 @@ venom_status_t venom_import(const uint16_t* values_dev, const uint16_t* columns_
 venom_status_t venom_export(const venom_handle_t* h, uint16_t* values_dev, uint16_t* columns_dev,
                             uint32_t* meta_dev, void* stream);
 
+/* Section 3, the two pruning stages, as one-shot magnitude pruning (the policy of the energy
+ * study of section 5): for every V x M block keep the 4 columns of largest L1 mass over the V rows,
+ * then in every row the 2 entries of largest magnitude among those 4; ties go to the smaller
+ * index.  Writes mask (R x K bytes, 1 = keep, exactly 2 per row and group: always legal for
+ * venom_compress).  Optionally accumulates, per block row, the kept and the total L1 mass as exact
+ * integers in units of 2^-24 (every fp16 is a multiple of it; Inf/NaN count as 2^40):
+ * energy = sum(kept) / sum(total).  kept_mass_dev / total_mass_dev: R/V uint64 each, or NULL.
+ * Needs R/V <= 65535.  Asynchronous on `stream`. */
+venom_status_t venom_prune(const void* A_f16_dev, int64_t lda, int64_t R, int64_t K, int V, int N, int M,
+                           uint8_t* mask_dev, int64_t ldm, uint64_t* kept_mass_dev, uint64_t* total_mass_dev,
+                           void* stream);
+
 /* Section 3 read backwards: expand to the dense masked R x K fp16 matrix (+0 outside the
  * structure), lda >= K.  Reads the KERNEL's packed copies, so it also checks the packing.
  * Needs V in {32, 64, 96, 128} (else VENOM_ERR_UNSUPPORTED).  Asynchronous on `stream`. */

@@ -22,7 +22,7 @@ STATUS_NAMES = {
  VENOM_ERR_WORKSPACE, VENOM_ERR_HIP) = range(1, 8)
 
 # every symbol include/venom.h declares
-EXPORTS = ("venom_workspace_bytes", "venom_compress", "venom_import", "venom_export", "venom_decompress",
+EXPORTS = ("venom_workspace_bytes", "venom_prune", "venom_compress", "venom_import", "venom_export", "venom_decompress",
            "venom_spmm", "venom_spmm_variant", "venom_spmm_bias_act", "venom_spmm_variant_count", "venom_spmm_variant_name",
            "venom_get_info", "venom_destroy", "venom_status_string")
 
@@ -55,6 +55,8 @@ def lib() -> ctypes.CDLL:
     L.venom_workspace_bytes.argtypes = [c_int64, c_int64, c_int, c_int, c_int, POINTER(c_size_t)]
     L.venom_compress.argtypes = [c_void_p, c_int64, c_void_p, c_int64, c_int64, c_int64, c_int, c_int, c_int,
                                  c_void_p, c_size_t, c_void_p, POINTER(c_void_p), POINTER(Violation)]
+    L.venom_prune.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_int, c_int, c_int, c_void_p, c_int64, c_void_p,
+                              c_void_p, c_void_p]
     L.venom_import.argtypes = [c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int, c_int, c_int, c_void_p,
                                c_size_t, c_void_p, POINTER(c_void_p)]
     L.venom_export.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
@@ -72,7 +74,7 @@ def lib() -> ctypes.CDLL:
     L.venom_destroy.restype = None
     L.venom_status_string.argtypes = [c_int]
     L.venom_status_string.restype = c_char_p
-    for name in ("venom_workspace_bytes", "venom_compress", "venom_import", "venom_export", "venom_decompress",
+    for name in ("venom_workspace_bytes", "venom_prune", "venom_compress", "venom_import", "venom_export", "venom_decompress",
                  "venom_spmm", "venom_spmm_variant", "venom_spmm_bias_act", "venom_spmm_variant_count", "venom_get_info"):
         getattr(L, name).restype = c_int
     _lib = L
@@ -146,6 +148,30 @@ def venom_compress(A, mask, V, N, M, stream=None) -> Handle:
     h = Handle(out, ws, R, K, V, N, M)
     h._owner = ws_owner
     return h
+
+
+def venom_prune(A, V, N, M, stream=None):
+    """Magnitude pruning of A (R x K float16 CUDA tensor) to V:N:M.  Returns (mask uint8 R x K,
+    kept_mass int64 [R/V], total_mass int64 [R/V]); the masses are exact integers in units of 2^-24."""
+    import torch
+    assert A.is_cuda and A.dtype == torch.float16 and A.dim() == 2 and A.stride(1) == 1
+    R, K = A.shape
+    mask = torch.empty((R, K), dtype=torch.uint8, device=A.device)
+    nb = max(R // V, 1) if V > 0 else 1
+    kept = torch.empty(nb, dtype=torch.int64, device=A.device)
+    total = torch.empty(nb, dtype=torch.int64, device=A.device)
+    st = lib().venom_prune(_ptr(A), A.stride(0) if R > 1 else max(K, A.stride(0)), R, K, V, N, M, _ptr(mask), K,
+                           _ptr(kept), _ptr(total), _stream_ptr(stream))
+    if st != VENOM_OK:
+        raise VenomError(st, "venom_prune")
+    return mask, kept, total
+
+
+def energy(kept_mass, total_mass) -> float:
+    """The energy metric from the per-block-row masses venom_prune returns (summed as Python integers)."""
+    k = sum(int(x) for x in kept_mass.cpu().tolist())
+    t = sum(int(x) for x in total_mass.cpu().tolist())
+    return k / t if t else 1.0
 
 
 def venom_import(values, columns, meta, R, K, V, N, M, stream=None) -> Handle:

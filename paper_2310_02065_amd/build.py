@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvenom.so")
-SOURCES = ["venom_api.hip", "venom_format.hip", "venom_spmm.hip"]
+SOURCES = ["venom_api.hip", "venom_format.hip", "venom_prune.hip", "venom_spmm.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

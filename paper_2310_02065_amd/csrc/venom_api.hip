@@ -46,6 +46,23 @@ venom_status_t venom_workspace_bytes(int64_t R, int64_t K, int V, int N, int M, 
   return VENOM_OK;
 }
 
+venom_status_t venom_prune(const void* A_f16_dev, int64_t lda, int64_t R, int64_t K, int V, int N, int M,
+                           uint8_t* mask_dev, int64_t ldm, uint64_t* kept_mass_dev, uint64_t* total_mass_dev,
+                           void* stream) {
+  venom_status_t s = check_shape(R, K, V, N, M);
+  if (s != VENOM_OK) return s;
+  if ((R > 0 && K > 0) && (!A_f16_dev || !mask_dev)) return VENOM_ERR_INVALID_ARG;
+  if (lda < K || ldm < K) return VENOM_ERR_SHAPE;
+  if (!aligned(A_f16_dev, 2) || !aligned(kept_mass_dev, 8) || !aligned(total_mass_dev, 8)) return VENOM_ERR_UNSUPPORTED;
+  if (R / V > 65535) return VENOM_ERR_UNSUPPORTED;   // block rows ride on the grid's y dimension
+  static_assert(sizeof(unsigned long long) == sizeof(uint64_t), "64-bit masses");
+  const hipError_t e = venom::launch_prune(static_cast<const uint16_t*>(A_f16_dev), lda, R, K, V, M, mask_dev, ldm,
+                                           reinterpret_cast<unsigned long long*>(kept_mass_dev),
+                                           reinterpret_cast<unsigned long long*>(total_mass_dev),
+                                           static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? VENOM_OK : VENOM_ERR_HIP;
+}
+
 venom_status_t venom_compress(const void* A_f16_dev, int64_t lda, const uint8_t* mask_dev, int64_t ldm, int64_t R,
                               int64_t K, int V, int N, int M, void* workspace_dev, size_t workspace_bytes,
                               void* stream, venom_handle_t** out, venom_violation_t* viol) {

@@ -53,6 +53,10 @@ hipError_t launch_compress(const uint16_t* A, int64_t lda, const uint8_t* mask, 
 hipError_t launch_pack(const venom_handle& h, hipStream_t st);
 hipError_t launch_decompress(const venom_handle& h, uint16_t* A, int64_t lda, hipStream_t st);
 
+// ---- pruning (venom_prune.hip)
+hipError_t launch_prune(const uint16_t* A, int64_t lda, int64_t R, int64_t K, int V, int M, uint8_t* mask, int64_t ldm,
+                        unsigned long long* kept_mass, unsigned long long* total_mass, hipStream_t st);
+
 // ---- product kernels (venom_spmm.hip)
 int spmm_variant_count();
 const char* spmm_variant_name(int v);

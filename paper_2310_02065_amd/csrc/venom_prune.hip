@@ -1,0 +1,117 @@
+// One-shot magnitude pruning of a dense fp16 matrix to V:N:M (paper section 3: per V x M block keep
+// the four most significant columns, then per row the two most meaningful of those four) and the
+// masses the energy metric of section 5 is made of.
+//
+// "Most significant" is read as the column's L1 mass over the V rows; ties go to the smaller
+// index.  Every fp16 is an integer multiple of 2^-24, so magnitudes are handled as integers in
+// that unit (Inf and NaN count as 2^40, above any finite value): the masses are exact, no
+// summation order exists, and the mask is a pure function of the bits.
+#include "venom_internal.h"
+
+namespace venom {
+
+constexpr int kPruneMaxCols = 1024;   // columns (groups x M) one workgroup looks at
+
+__device__ __forceinline__ unsigned long long magnitude_units(uint16_t bits) {
+  const unsigned e = (bits >> 10) & 31u, f = bits & 1023u;
+  if (e == 0) return f;
+  if (e == 31) return 1ull << 40;
+  return (unsigned long long)(1024u + f) << (e - 1);
+}
+
+__global__ void zero_u64_kernel(unsigned long long* a, unsigned long long* b, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) {
+    if (a) a[i] = 0;
+    if (b) b[i] = 0;
+  }
+}
+
+// One workgroup per (block row b, chunk of `gpw` groups): V rows x gpw*M columns.
+//   phase 1: column masses into LDS (64-bit integer adds), the block's total mass
+//   phase 2: one thread per group picks the 4 columns: largest mass first, smaller index on ties,
+//            then sorted ascending
+//   phase 3: one thread per (row, group): the 2 largest magnitudes among the 4, smaller position on
+//            ties; the mask segment is zero-filled first, then the kept positions are set
+__global__ void __launch_bounds__(256) prune_kernel(const uint16_t* __restrict__ A, int64_t lda, int V, int M,
+                                                    int64_t G, int gpw, uint8_t* __restrict__ mask, int64_t ldm,
+                                                    unsigned long long* __restrict__ kept_mass,
+                                                    unsigned long long* __restrict__ total_mass) {
+  __shared__ unsigned long long mass[kPruneMaxCols];
+  __shared__ int sel[kPruneMaxCols / kSelCols][kSelCols];
+  __shared__ unsigned long long wg_total, wg_kept;
+  const int64_t chunk = blockIdx.x, b = blockIdx.y;
+  const int tid = threadIdx.x;
+  const int64_t g0 = chunk * gpw;
+  const int ng = (int)((G - g0) < gpw ? (G - g0) : gpw);
+  const int span = ng * M;
+
+  for (int i = tid; i < span; i += blockDim.x) mass[i] = 0;
+  if (tid == 0) { wg_total = 0; wg_kept = 0; }
+  __syncthreads();
+  unsigned long long my_total = 0;
+  for (int64_t i = tid; i < (int64_t)V * span; i += blockDim.x) {
+    const int v = (int)(i / span), c = (int)(i % span);
+    const unsigned long long m = magnitude_units(A[(b * V + v) * lda + g0 * M + c]);
+    mask[(b * V + v) * ldm + g0 * M + c] = 0;
+    if (m) atomicAdd(&mass[c], m);
+    my_total += m;
+  }
+  if (my_total) atomicAdd(&wg_total, my_total);
+  __syncthreads();
+  if (tid < ng) {
+    const unsigned long long* mg = mass + tid * M;
+    int s[kSelCols];
+    for (int k = 0; k < kSelCols; ++k) {
+      int best = -1;
+      for (int c = 0; c < M; ++c) {
+        bool taken = false;
+        for (int j = 0; j < k; ++j) taken |= s[j] == c;
+        if (!taken && (best < 0 || mg[c] > mg[best])) best = c;   // strict >: the smaller index wins ties
+      }
+      s[k] = best;
+    }
+    for (int i = 1; i < kSelCols; ++i)                             // ascending order
+      for (int j = i; j > 0 && s[j - 1] > s[j]; --j) { const int t = s[j]; s[j] = s[j - 1]; s[j - 1] = t; }
+    for (int k = 0; k < kSelCols; ++k) sel[tid][k] = s[k];
+  }
+  __syncthreads();   // also orders the zero fill of the mask before the ones below
+  unsigned long long my_kept = 0;
+  for (int i = tid; i < V * ng; i += blockDim.x) {
+    const int v = i / ng, t = i % ng;
+    const int64_t base = (b * V + v) * lda + (g0 + t) * M;
+    unsigned long long m[kSelCols];
+    for (int p = 0; p < kSelCols; ++p) m[p] = magnitude_units(A[base + sel[t][p]]);
+    int p0 = 0;
+    for (int p = 1; p < kSelCols; ++p) if (m[p] > m[p0]) p0 = p;
+    int p1 = p0 == 0 ? 1 : 0;
+    for (int p = 0; p < kSelCols; ++p) if (p != p0 && m[p] > m[p1]) p1 = p;
+    uint8_t* mrow = mask + (b * V + v) * ldm + (g0 + t) * M;
+    mrow[sel[t][p0]] = 1;
+    mrow[sel[t][p1]] = 1;
+    my_kept += m[p0] + m[p1];
+  }
+  if (my_kept) atomicAdd(&wg_kept, my_kept);
+  __syncthreads();
+  if (tid == 0) {
+    if (total_mass && wg_total) atomicAdd(&total_mass[b], wg_total);
+    if (kept_mass && wg_kept) atomicAdd(&kept_mass[b], wg_kept);
+  }
+}
+
+hipError_t launch_prune(const uint16_t* A, int64_t lda, int64_t R, int64_t K, int V, int M, uint8_t* mask, int64_t ldm,
+                        unsigned long long* kept_mass, unsigned long long* total_mass, hipStream_t st) {
+  const int64_t Rb = R / V, G = K / M;
+  if (kept_mass || total_mass)
+    hipLaunchKernelGGL(zero_u64_kernel, dim3((unsigned)((Rb + 255) / 256)), dim3(256), 0, st, kept_mass, total_mass, Rb);
+  if (Rb == 0 || G == 0) return hipGetLastError();
+  int gpw = kPruneMaxCols / M;
+  if (gpw > kStepGroups) gpw = kStepGroups;
+  if (gpw < 1) gpw = 1;
+  const int64_t chunks = (G + gpw - 1) / gpw;
+  hipLaunchKernelGGL(prune_kernel, dim3((unsigned)chunks, (unsigned)Rb), dim3(256), 0, st, A, lda, V, M, G, gpw, mask, ldm,
+                     kept_mass, total_mass);
+  return hipGetLastError();
+}
+
+}  // namespace venom
