@@ -315,3 +315,17 @@ def prune(A_bits: np.ndarray, V: int, M: int):
                     kept += int(blk[v, cols[p]])
     total = int(sum(int(x) for x in mag.sum(axis=1)))
     return mask, kept, total
+
+
+# ---------------------------------------------------------------------------------------------
+# The sparse layer as a linear layer sees it (section 7.2: the V:N:M weight replaces the weight of
+# a linear layer; activations arrive token-major, one row of K features per token):
+#     Y[t][r] = act( sum_k X[t][k] * A[r][k] + bias[r] ),   Y is tokens x R.
+def linear_fp64(values, columns, meta, R, K, V, M, X_bits, bias_bits=None, activation="none"):
+    """Returns (Y, E_y), both tokens x R: the product with B = X^T, the epilogue, transposed."""
+    X_bits = np.asarray(X_bits)
+    if X_bits.ndim != 2 or X_bits.shape[1] != K:
+        raise ValueError("X must be tokens x K")
+    C_star, E = spmm_fp64(values, columns, meta, R, K, V, M, np.ascontiguousarray(X_bits.T))
+    Y, Ey = epilogue_fp64(C_star, E, bias_bits, activation)
+    return np.ascontiguousarray(Y.T), np.ascontiguousarray(Ey.T)

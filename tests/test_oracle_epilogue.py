@@ -71,3 +71,25 @@ def test_planted_mistakes_in_the_epilogue_are_caught():
     no_half = C + b[:, None]
     for bad in (wrong_axis, act_before_bias, no_half):
         assert np.abs(bad - good).max() > 1e-2
+
+
+def test_linear_layer_view_is_x_times_masked_weight_transposed():
+    from paper_2310_02065_amd import inputs
+    R, K, T, V, M = 32, 48, 5, 16, 6
+    A, mask, _ = inputs.gen_problem(R, K, 8, V, M, 1.0, seed=21)
+    rng = np.random.default_rng(4)
+    X = rng.standard_normal((T, K)).astype(np.float16)
+    bias = rng.standard_normal(R).astype(np.float16)
+    vals, cols, meta = o.compress(A, mask, V, M)
+    Y, Ey = o.linear_fp64(vals, cols, meta, R, K, V, M, X.view(np.uint16), bias.view(np.uint16), "none")
+    W = np.where(mask != 0, A.view(np.float16).astype(np.float64), 0.0)          # dense masked weight, no format
+    ref = np.zeros((T, R))
+    for t in range(T):
+        for r in range(R):
+            ref[t, r] = sum(float(X[t, k]) * W[r, k] for k in range(K)) + float(bias[r])
+    assert Y.shape == (T, R) and np.allclose(Y, ref, rtol=0, atol=1e-12)
+    assert (Ey >= np.abs(Y) - 1e-12).all()
+    Yg, _ = o.linear_fp64(vals, cols, meta, R, K, V, M, X.view(np.uint16), bias.view(np.uint16), "gelu")
+    assert np.allclose(Yg, o.gelu_erf(ref), atol=1e-12)
+    with pytest.raises(ValueError):
+        o.linear_fp64(vals, cols, meta, R, K, V, M, X.view(np.uint16)[:, :-1])
