@@ -130,6 +130,18 @@ typedef enum { VENOM_ACT_NONE = 0, VENOM_ACT_GELU = 1, VENOM_ACT_GELU_TANH = 2 }
 venom_status_t venom_spmm_bias_act(const venom_handle_t* h, const void* B_f16_dev, int64_t ldb, int64_t C_cols,
                                    const void* bias_f16_dev, int activation, void* C_dev, int64_t ldc, int c_dtype,
                                    int variant, void* stream);
+/* The sparse layer as a linear layer sees it (section 7.2: the V:N:M weight replaces the weight of
+ * a linear layer): activations token-major, X = tokens x K fp16 (ldx >= K), output token-major,
+ * Y = tokens x R (ldy >= R), fp16 (y_dtype 0) or fp32 (1):
+ *     Y = act(X . A^T + bias),  bias one fp16 entry per output feature (R), or NULL.
+ * The gather needs rows of X^T, so X is first transposed into `scratch_dev` (caller-owned device
+ * memory, 16-byte aligned, at least venom_linear_scratch_bytes() bytes, overwritten); the product
+ * kernel then writes Y transposed straight from its accumulators.  tokens % 8 == 0; Y and ldy
+ * aligned to 4 elements; V in {32, 64, 96, 128}.  Asynchronous on `stream`, allocates nothing. */
+venom_status_t venom_linear_scratch_bytes(const venom_handle_t* h, int64_t tokens, size_t* bytes);
+venom_status_t venom_linear(const venom_handle_t* h, const void* X_f16_dev, int64_t ldx, int64_t tokens,
+                            const void* bias_f16_dev, int activation, void* Y_dev, int64_t ldy, int y_dtype,
+                            void* scratch_dev, size_t scratch_bytes, void* stream);
 int venom_spmm_variant_count(void);
 /* Name of a variant ("v128_c512", ...) or NULL. */
 const char* venom_spmm_variant_name(int variant);

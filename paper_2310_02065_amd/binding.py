@@ -23,7 +23,8 @@ STATUS_NAMES = {
 
 # every symbol include/venom.h declares
 EXPORTS = ("venom_workspace_bytes", "venom_prune", "venom_compress", "venom_import", "venom_export", "venom_decompress",
-           "venom_spmm", "venom_spmm_variant", "venom_spmm_bias_act", "venom_spmm_variant_count", "venom_spmm_variant_name",
+           "venom_spmm", "venom_spmm_variant", "venom_spmm_bias_act", "venom_linear_scratch_bytes", "venom_linear",
+           "venom_spmm_variant_count", "venom_spmm_variant_name",
            "venom_get_info", "venom_destroy", "venom_status_string")
 
 
@@ -65,6 +66,9 @@ def lib() -> ctypes.CDLL:
     L.venom_spmm_variant.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_void_p, c_int64, c_int, c_int, c_void_p]
     L.venom_spmm_bias_act.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_void_p, c_int, c_void_p, c_int64, c_int,
                                       c_int, c_void_p]
+    L.venom_linear_scratch_bytes.argtypes = [c_void_p, c_int64, POINTER(c_size_t)]
+    L.venom_linear.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_void_p, c_int, c_void_p, c_int64, c_int, c_void_p,
+                               c_size_t, c_void_p]
     L.venom_spmm_variant_count.argtypes = []
     L.venom_spmm_variant_name.argtypes = [c_int]
     L.venom_spmm_variant_name.restype = c_char_p
@@ -234,6 +238,32 @@ def venom_spmm(h: Handle, B, out=None, out_dtype=None, variant=-1, stream=None, 
                                    c_dtype, variant, _stream_ptr(stream))
     if st != VENOM_OK:
         raise VenomError(st, "venom_spmm")
+    return out
+
+
+def venom_linear(h: Handle, X, bias=None, activation="none", out=None, out_dtype=None, scratch=None, stream=None):
+    """Y = act(X . A^T + bias): X tokens x K float16 CUDA tensor, Y tokens x R (token-major in and out).
+    `scratch` (uint8 CUDA tensor) receives X transposed; allocated here when not given."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.stride(1) == 1 and X.shape[1] == h.K
+    tokens = X.shape[0]
+    if out is None:
+        out = torch.empty((tokens, h.R), dtype=out_dtype or torch.float16, device=X.device)
+    assert out.dtype in (torch.float16, torch.float32) and out.stride(1) == 1 and out.shape == (tokens, h.R)
+    need = c_size_t(0)
+    st = lib().venom_linear_scratch_bytes(h.ptr, tokens, byref(need))
+    if st != VENOM_OK:
+        raise VenomError(st, "venom_linear_scratch_bytes")
+    if scratch is None:
+        scratch = torch.empty(max(need.value, 16), dtype=torch.uint8, device=X.device)
+    if bias is not None:
+        assert bias.is_cuda and bias.dtype == torch.float16 and bias.dim() == 1 and bias.shape[0] == h.R
+    ldx = X.stride(0) if tokens > 1 else max(h.K, X.stride(0))
+    ldy = out.stride(0) if tokens > 1 else max(h.R, out.stride(0))
+    st = lib().venom_linear(h.ptr, _ptr(X), ldx, tokens, _ptr(bias), ACTIVATIONS[activation], _ptr(out), ldy,
+                            1 if out.dtype == torch.float32 else 0, _ptr(scratch), scratch.numel(), _stream_ptr(stream))
+    if st != VENOM_OK:
+        raise VenomError(st, "venom_linear")
     return out
 
 

@@ -170,8 +170,42 @@ venom_status_t venom_spmm_bias_act(const venom_handle_t* h, const void* B_f16_de
   const size_t esz = c_dtype == 1 ? 4 : 2;
   if (!aligned(B_f16_dev, 16) || !aligned(C_dev, 16) || (ldb * 2) % 16 != 0 || (ldc * esz) % 16 != 0)
     return VENOM_ERR_UNSUPPORTED;
-  return venom::launch_spmm(*h, B_f16_dev, ldb, C_cols, bias_f16_dev, activation, C_dev, ldc, c_dtype, variant,
+  return venom::launch_spmm(*h, B_f16_dev, ldb, C_cols, bias_f16_dev, activation, C_dev, ldc, c_dtype, 0, variant,
                             static_cast<hipStream_t>(stream));
+}
+
+venom_status_t venom_linear_scratch_bytes(const venom_handle_t* h, int64_t tokens, size_t* bytes) {
+  if (!h || !bytes || tokens < 0) return VENOM_ERR_INVALID_ARG;
+  *bytes = (size_t)h->K * (size_t)((tokens + 7) / 8 * 8) * 2;
+  return VENOM_OK;
+}
+
+venom_status_t venom_linear(const venom_handle_t* h, const void* X_f16_dev, int64_t ldx, int64_t tokens,
+                            const void* bias_f16_dev, int activation, void* Y_dev, int64_t ldy, int y_dtype,
+                            void* scratch_dev, size_t scratch_bytes, void* stream) {
+  if (!h) return VENOM_ERR_INVALID_ARG;
+  if (y_dtype != 0 && y_dtype != 1) return VENOM_ERR_INVALID_ARG;
+  if (activation != VENOM_ACT_NONE && activation != VENOM_ACT_GELU && activation != VENOM_ACT_GELU_TANH)
+    return VENOM_ERR_INVALID_ARG;
+  if (tokens < 0) return VENOM_ERR_INVALID_ARG;
+  if (tokens < 1) return VENOM_ERR_SHAPE;
+  if (ldx < h->K || ldy < h->R) return VENOM_ERR_SHAPE;
+  if ((h->K > 0 && !X_f16_dev) || (h->R > 0 && !Y_dev)) return VENOM_ERR_INVALID_ARG;
+  if (h->V % venom::kTileRows != 0 || tokens % 8 != 0) return VENOM_ERR_UNSUPPORTED;
+  if (tokens > 65535 * 64) return VENOM_ERR_UNSUPPORTED;   // token tiles ride on the transpose grid's y dimension
+  const size_t esz = y_dtype == 1 ? 4 : 2;
+  // a lane stores runs of 4 consecutive features: 8 bytes (fp16) or 16 bytes (fp32)
+  if (!aligned(X_f16_dev, 2) || !aligned(Y_dev, 4 * esz) || (ldy * esz) % (4 * esz) != 0) return VENOM_ERR_UNSUPPORTED;
+  if (bias_f16_dev && !aligned(bias_f16_dev, 8)) return VENOM_ERR_UNSUPPORTED;
+  size_t need = 0;
+  venom_linear_scratch_bytes(h, tokens, &need);
+  if (!scratch_dev || !aligned(scratch_dev, 16) || scratch_bytes < need) return VENOM_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int64_t ldbt = (tokens + 7) / 8 * 8;
+  if (venom::launch_transpose_tokens(static_cast<const uint16_t*>(X_f16_dev), ldx, tokens, h->K,
+                                     static_cast<uint16_t*>(scratch_dev), ldbt, st) != hipSuccess)
+    return VENOM_ERR_HIP;
+  return venom::launch_spmm(*h, scratch_dev, ldbt, tokens, bias_f16_dev, activation, Y_dev, ldy, y_dtype, 1, -1, st);
 }
 
 venom_status_t venom_spmm_variant(const venom_handle_t* h, const void* B_f16_dev, int64_t ldb, int64_t C_cols,

@@ -61,7 +61,10 @@ hipError_t launch_prune(const uint16_t* A, int64_t lda, int64_t R, int64_t K, in
 int spmm_variant_count();
 const char* spmm_variant_name(int v);
 // returns VENOM_OK / VENOM_ERR_UNSUPPORTED / VENOM_ERR_HIP
+// tokens_major != 0: C is written transposed (C[column][row], leading dimension ldc counts rows of A)
 venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, int64_t Ccols, const void* bias, int act,
-                           void* C, int64_t ldc, int c_dtype, int variant, hipStream_t st);
+                           void* C, int64_t ldc, int c_dtype, int tokens_major, int variant, hipStream_t st);
+hipError_t launch_transpose_tokens(const uint16_t* X, int64_t ldx, int64_t tokens, int64_t K, uint16_t* BT, int64_t ldbt,
+                                   hipStream_t st);
 
 }  // namespace venom

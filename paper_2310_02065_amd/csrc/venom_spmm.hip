@@ -141,9 +141,12 @@ struct TileWalk {
   }
 };
 
-template <int VT, int NC, int NPB, int NA, bool OUT_F32, bool EPI>
+// MODE 0: the plain product; 1: fused bias / activation; 2: the same with C written transposed
+// (token-major).  Separate instantiations: the plain kernel carries none of the epilogue code.
+template <int VT, int NC, int NPB, int NA, bool OUT_F32, int MODE>
 __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams p) {
   static_assert(NC == 2 || NC == 4 || NC == 8, "consumer waves per workgroup");
+  constexpr bool EPI = MODE != 0;
   static_assert(VT >= 1 && VT <= kMaxTiles, "32-row tiles per block row");
   static_assert(NA >= 4, "the A ring holds the record being read, the next one, and records in flight");
   constexpr int BSC = 64 * NC;                     // columns of C per workgroup
@@ -458,50 +461,92 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
 #ifdef VENOM_ABLATE
       if ((kAbl & 16) && acc[0][0][0] != 12345.f) continue;
 #endif
+      // everything below is per-tile work: keep its index arithmetic from being hoisted out of the
+      // tile loop, where it would sit in registers the k-loop needs
+      int ln = lane;
+      asm volatile("" : "+v"(ln));
       int ct, br;
       tw.locate(p, t, ct, br);
       const int64_t row0 = (int64_t)br * VT * 32;
       const int64_t col0 = (int64_t)ct * BSC + wave * 64;
       // fused epilogue (the layer's bias, one per output row, then the activation), in fp32 on
-      // the accumulators, one 32-row tile at a time right before it is stored: a lane holds rows
-      // 8j + 4*(lane/32) + 0..3 of the tile
+      // the accumulators, one 32-row tile at a time right before it is stored: a ln holds rows
+      // 8j + 4*(ln/32) + 0..3 of the tile
       auto finish = [&](int tr) {
         if constexpr (!EPI) return;                // the plain product compiles without any of this
         if (p.bias) {
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
-            const half4 b4 = *reinterpret_cast<const half4*>(p.bias + row0 + tr * 32 + 8 * j + 4 * (lane >> 5));
+            const half4 b4 = *reinterpret_cast<const half4*>(p.bias + row0 + tr * 32 + 8 * j + 4 * (ln >> 5));
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
               acc[tr][0][4 * j + i] += (float)b4[i];
               acc[tr][1][4 * j + i] += (float)b4[i];
             }
+            __builtin_amdgcn_sched_barrier(0);
           }
         }
+        // (scheduling fences keep the evaluations from being interleaved by the dozen: their
+        // temporaries would push accumulators out of registers, for the whole kernel)
         if (p.act == VENOM_ACT_GELU) {
 #pragma unroll
           for (int tc = 0; tc < 2; ++tc)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[tr][tc][v] = gelu_by_definition(acc[tr][tc][v]);
+            for (int v = 0; v < 16; ++v) {
+              acc[tr][tc][v] = gelu_by_definition(acc[tr][tc][v]);
+              if ((v & 1) == 1) __builtin_amdgcn_sched_barrier(0);
+            }
         } else if (p.act == VENOM_ACT_GELU_TANH) {
 #pragma unroll
           for (int tc = 0; tc < 2; ++tc)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[tr][tc][v] = gelu_tanh_form(acc[tr][tc][v]);
+            for (int v = 0; v < 16; ++v) {
+              acc[tr][tc][v] = gelu_tanh_form(acc[tr][tc][v]);
+              if ((v & 1) == 1) __builtin_amdgcn_sched_barrier(0);
+            }
         }
       };
-      if constexpr (OUT_F32) {
+      if constexpr (MODE == 2) {
+        // Token-major output Y[token][feature] = C transposed: a ln owns one column of C (a
+        // token) and, per 32-row tile, four runs of 4 consecutive rows (features): each run is one
+        // 8-byte (fp16) or 16-byte (fp32) store straight from the accumulators; the two half-waves
+        // write neighbouring runs, the tiles of a block row continue the same 2*V bytes of a token.
+#pragma unroll
+        for (int tr = 0; tr < VT; ++tr) {
+          finish(tr);
+#pragma unroll
+          for (int tc = 0; tc < 2; ++tc) {
+            const int64_t tok = col0 + tc * 32 + (ln & 31);
+            if (tok < p.Ccols) {
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                const int64_t feat = row0 + tr * 32 + 8 * q + 4 * (ln >> 5);
+                if constexpr (OUT_F32) {
+                  typedef float f32x4 __attribute__((ext_vector_type(4)));
+                  const f32x4 o = {acc[tr][tc][4 * q], acc[tr][tc][4 * q + 1], acc[tr][tc][4 * q + 2], acc[tr][tc][4 * q + 3]};
+                  *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.C) + tok * p.ldc + feat) = o;
+                } else {
+                  const half4 o = {(_Float16)acc[tr][tc][4 * q], (_Float16)acc[tr][tc][4 * q + 1],
+                                   (_Float16)acc[tr][tc][4 * q + 2], (_Float16)acc[tr][tc][4 * q + 3]};
+                  *reinterpret_cast<half4*>(reinterpret_cast<_Float16*>(p.C) + tok * p.ldc + feat) = o;
+                }
+              }
+            }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      } else if constexpr (OUT_F32) {
         float* Cf = reinterpret_cast<float*>(p.C);
 #pragma unroll
         for (int tr = 0; tr < VT; ++tr) {
           finish(tr);
 #pragma unroll
           for (int tc = 0; tc < 2; ++tc) {
-            const int64_t col = col0 + tc * 32 + (lane & 31);
+            const int64_t col = col0 + tc * 32 + (ln & 31);
             if (col < p.Ccols) {
 #pragma unroll
               for (int v = 0; v < 16; ++v) {
-                const int64_t row = row0 + tr * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                const int64_t row = row0 + tr * 32 + 8 * (v >> 2) + 4 * (ln >> 5) + (v & 3);
                 Cf[row * p.ldc + col] = acc[tr][tc][v];
               }
             }
@@ -515,17 +560,17 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
         // which write rows r and r+4, use different banks.
         char* stg = const_cast<char*>(sb) + wave * 4096;
         _Float16* Ch = reinterpret_cast<_Float16*>(p.C);
-        const int chunk = lane & 7, rsub = lane >> 3;
+        const int chunk = ln & 7, rsub = ln >> 3;
         const int64_t col = col0 + chunk * 8;
 #pragma unroll
         for (int tr = 0; tr < VT; ++tr) {
           finish(tr);
 #pragma unroll
           for (int tc = 0; tc < 2; ++tc) {
-            const int c = tc * 32 + (lane & 31);
+            const int c = tc * 32 + (ln & 31);
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-              const int r = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+              const int r = 8 * (v >> 2) + 4 * (ln >> 5) + (v & 3);
               const int sw = ((c >> 3) ^ (4 * ((r >> 2) & 1)));
               *reinterpret_cast<_Float16*>(stg + r * 128 + sw * 16 + (c & 7) * 2) =
                   (_Float16)acc[tr][tc][v];        // one rounding, nearest-even
@@ -565,7 +610,7 @@ struct Variant {
   int bsc;     // columns per workgroup
   int threads;
   int lds;     // dynamic LDS bytes
-  void (*fn[2][2])(SpmmParams);   // [fp32 output][fused bias/activation]
+  void (*fn[2][3])(SpmmParams);   // [fp32 output][mode]
 };
 
 template <int VT, int NC, int NA>
@@ -575,8 +620,10 @@ constexpr int lds_bytes() {   // B ring, A ring, row-id ring (the output staging
 
 #define VARIANT(NAME, VT, NC, NPB, NA)                                                         \
   { NAME, (VT) * 32, 64 * (NC), 64 * ((NC) + (NPB) + 1), lds_bytes<VT, NC, NA>(),                \
-    { { spmm_kernel<VT, NC, NPB, NA, false, false>, spmm_kernel<VT, NC, NPB, NA, false, true> },       \
-      { spmm_kernel<VT, NC, NPB, NA, true, false>, spmm_kernel<VT, NC, NPB, NA, true, true> } } }
+    { { spmm_kernel<VT, NC, NPB, NA, false, 0>, spmm_kernel<VT, NC, NPB, NA, false, 1>,                \
+        spmm_kernel<VT, NC, NPB, NA, false, 2> },                                                    \
+      { spmm_kernel<VT, NC, NPB, NA, true, 0>, spmm_kernel<VT, NC, NPB, NA, true, 1>,                  \
+        spmm_kernel<VT, NC, NPB, NA, true, 2> } } }
 
 static const Variant kVariants[] = {
     VARIANT("v128_c512", 4, 8, 3, 6), VARIANT("v128_c256", 4, 4, 2, 9), VARIANT("v128_c128", 4, 2, 1, 10),
@@ -605,7 +652,7 @@ static int pick_variant(int V, int64_t Ccols, int64_t nbr) {
 }
 
 venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, int64_t Ccols, const void* bias, int act,
-                           void* C, int64_t ldc, int c_dtype, int variant, hipStream_t st) {
+                           void* C, int64_t ldc, int c_dtype, int tokens_major, int variant, hipStream_t st) {
   const Layout& L = h.lay;
   if (!L.packed) return VENOM_ERR_UNSUPPORTED;
   if (L.R == 0 || Ccols == 0) return VENOM_OK;
@@ -653,16 +700,16 @@ venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, in
   const unsigned grid = (unsigned)(wg_per_xcd * kNumXcd);
   // a workgroup numbers the k-steps of all its tiles with one 32-bit counter
   if ((p.per_xcd + wg_per_xcd - 1) / wg_per_xcd * L.steps >= ((int64_t)1 << 30)) return VENOM_ERR_UNSUPPORTED;
-  const int epi = (bias != nullptr || act != VENOM_ACT_NONE) ? 1 : 0;
+  const int epi = tokens_major ? 2 : ((bias != nullptr || act != VENOM_ACT_NONE) ? 1 : 0);
   auto fn = var.fn[c_dtype == 1 ? 1 : 0][epi];
   if (var.lds > 64 * 1024) {
     // opting in to more than 64 KB of dynamic LDS is a per-function attribute (set once per device)
-    static bool opted_in[kNumVariants][4][16] = {};
-    if (dev < 0 || dev >= 16 || !opted_in[variant][2 * c_dtype + epi][dev]) {
+    static bool opted_in[kNumVariants][6][16] = {};
+    if (dev < 0 || dev >= 16 || !opted_in[variant][3 * c_dtype + epi][dev]) {
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
                               var.lds) != hipSuccess)
         return VENOM_ERR_HIP;
-      if (dev >= 0 && dev < 16) opted_in[variant][2 * c_dtype + epi][dev] = true;
+      if (dev >= 0 && dev < 16) opted_in[variant][3 * c_dtype + epi][dev] = true;
     }
   }
   const int launch_lds = var.lds;
@@ -680,6 +727,47 @@ venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, in
   }
 #endif
   return hipGetLastError() == hipSuccess ? VENOM_OK : VENOM_ERR_HIP;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Activations as a linear layer holds them, X[token][k], to the K x tokens row-major operand the
+// gather wants: 64 x 64 tiles through LDS, 4-byte accesses on both sides.
+__global__ void __launch_bounds__(256) transpose_tokens_kernel(const uint16_t* __restrict__ X, int64_t ldx, int64_t tokens,
+                                                               int64_t K, uint16_t* __restrict__ BT, int64_t ldbt) {
+  __shared__ uint16_t tile[64][66];                // [k][token], padded
+  const int64_t k0 = (int64_t)blockIdx.x * 64, tok0 = (int64_t)blockIdx.y * 64;
+  const int pair = threadIdx.x & 31, sub = threadIdx.x >> 5;
+  for (int r = sub; r < 64; r += 8) {               // r: token inside the tile, pair: two k
+    const int64_t tok = tok0 + r, k = k0 + 2 * pair;
+    uint16_t a = 0, b = 0;
+    if (tok < tokens) {
+      if (k + 1 < K && ((reinterpret_cast<uintptr_t>(X + tok * ldx + k) & 3) == 0)) {
+        const uint32_t w = *reinterpret_cast<const uint32_t*>(X + tok * ldx + k);
+        a = (uint16_t)w; b = (uint16_t)(w >> 16);
+      } else {
+        if (k < K) a = X[tok * ldx + k];
+        if (k + 1 < K) b = X[tok * ldx + k + 1];
+      }
+    }
+    tile[2 * pair][r] = a;
+    tile[2 * pair + 1][r] = b;
+  }
+  __syncthreads();
+  for (int r = sub; r < 64; r += 8) {               // r: k inside the tile, pair: two tokens
+    const int64_t k = k0 + r, tok = tok0 + 2 * pair;
+    if (k < K && tok < ldbt) {                       // ldbt is even and >= tokens: pad columns get zeros
+      const uint32_t w = (uint32_t)tile[r][2 * pair] | ((uint32_t)tile[r][2 * pair + 1] << 16);
+      *reinterpret_cast<uint32_t*>(BT + k * ldbt + tok) = w;
+    }
+  }
+}
+
+hipError_t launch_transpose_tokens(const uint16_t* X, int64_t ldx, int64_t tokens, int64_t K, uint16_t* BT, int64_t ldbt,
+                                   hipStream_t st) {
+  if (tokens == 0 || K == 0) return hipSuccess;
+  hipLaunchKernelGGL(transpose_tokens_kernel, dim3((unsigned)((K + 63) / 64), (unsigned)((ldbt + 63) / 64)), dim3(256), 0,
+                     st, X, ldx, tokens, K, BT, ldbt);
+  return hipGetLastError();
 }
 
 }  // namespace venom
