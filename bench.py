@@ -31,7 +31,7 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/),
 # scaled by the same counters read on a plain copy kernel; None where not measured yet.
-MEASURED_TRAFFIC_BYTES = {"gpt3": 1202692096}   # 998.7 MB read + 203.9 MB written
+MEASURED_TRAFFIC_BYTES = {"gpt3": 1287534336}   # 1086.2 MB read + 201.3 MB written
 
 
 def algorithmic_bytes(R, K, C, V, M, out_bytes=2):
@@ -43,8 +43,8 @@ def algorithmic_bytes(R, K, C, V, M, out_bytes=2):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="gpt3", help="gpt3 | bert_large | bert_base | tiny")
     ap.add_argument("--variant", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
