@@ -47,6 +47,7 @@ struct SpmmParams {
   int nbr, nct;            // block rows, column tiles
   int per_xcd;             // ceil(nbr*nct / 8)
   int stream_out;          // nonzero: non-temporal stores of C
+  int pad_row0;            // first gathered row of a tile's LAST k-step that lies past the end of K (32: none)
   const _Float16* bias;    // one entry per row of C, or null
   int act;                 // venom_activation_t
 #ifdef VENOM_ABLATE
@@ -90,6 +91,13 @@ __device__ __forceinline__ void wait_units_and_barrier(int k) {
   static_assert(MAXK * UNIT <= 63, "vmcnt is a 6-bit counter");
   if (k >= MAXK) wait_loads_and_barrier<MAXK * UNIT>();
   else if constexpr (MAXK > 0) wait_units_and_barrier<UNIT, MAXK - 1>(k);
+}
+// only the wait, for N = min(k, MAXK) * UNIT
+template <int UNIT, int MAXK>
+__device__ __forceinline__ void wait_units(int k) {
+  static_assert(MAXK * UNIT <= 63, "vmcnt is a 6-bit counter");
+  if (k >= MAXK) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(MAXK * UNIT) : "memory");
+  else if constexpr (MAXK > 0) wait_units<UNIT, MAXK - 1>(k);
 }
 __device__ __forceinline__ void barrier_only() { asm volatile("s_barrier" ::: "memory"); }
 // the same once every LDS read of this wave has returned (its reads of a stage must be over
@@ -343,7 +351,20 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
       // this producer's part of k-step g has landed when at most its loads of the later steps
       // (up to two) are pending
       const int left = G - 1 - g;
-      if (hi) wait_units_and_barrier<NBH, kStages - 2>(left);
+      if (p.pad_row0 < kStepRows && c_s == p.steps - 1) {
+        // The last k-step of a tile when K/M is not a multiple of 8: its trailing groups do not
+        // exist.  Their values are zero, but 0 x Inf is not, so the rows gathered for them (row 0
+        // of B, a valid address that keeps the load count exact) are overwritten with zeros once
+        // they have landed; every producer cleans the rows it loaded itself.
+        if (hi) wait_units<NBH, kStages - 2>(left);
+        else wait_units<NBL, kStages - 2>(left);
+        char* stage = smem + (g % kStages) * B_BYTES;
+#pragma unroll
+        for (int q = 0; q < NBH; ++q)
+          if ((q < NBL || hi) && ((pj + NPB * q) % NI) * RPI + rowsel >= p.pad_row0)
+            *reinterpret_cast<uint4*>(stage + (pj + NPB * q) * 1024 + lane * 16) = make_uint4(0, 0, 0, 0);
+        lgkm_drained_barrier();
+      } else if (hi) wait_units_and_barrier<NBH, kStages - 2>(left);
       else wait_units_and_barrier<NBL, kStages - 2>(left);
       // after the barrier the consumers are done with stage g-1: it takes step g+PB
       if (g + PB < G) {
@@ -467,6 +488,9 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
       asm volatile("" : "+v"(ln));
       int ct, br;
       tw.locate(p, t, ct, br);
+#ifdef VENOM_ABLATE
+      if (kAbl & 8192) { br = 0; ct = 0; }         // experiment: every tile writes block (0, 0) of C
+#endif
       const int64_t row0 = (int64_t)br * VT * 32;
       const int64_t col0 = (int64_t)ct * BSC + wave * 64;
       // fused epilogue (the layer's bias, one per output row, then the activation), in fp32 on
@@ -668,6 +692,7 @@ venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, in
   p.steps = (int)L.steps;
   p.bias = reinterpret_cast<const _Float16*>(bias);
   p.act = act;
+  p.pad_row0 = (L.G % kStepGroups) ? (int)(L.G % kStepGroups) * kSelCols : kStepRows;
   p.stream_out = L.steps >= 32;   // measured: +3 % at 48 k-steps per tile, -20 % at 8
 #ifdef VENOM_ABLATE
   p.k_rows = (int)h.K;

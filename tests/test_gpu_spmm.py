@@ -175,3 +175,28 @@ def test_epilogue_argument_errors():
     st = L.venom_spmm_bias_act(h.ptr, ctypes.c_void_p(to_dev_f16(B).data_ptr()), C, C,
                                ctypes.c_void_p(bias.data_ptr() + 2), 0, ctypes.c_void_p(out.data_ptr()), C, 0, -1, None)
     assert st == binding.VENOM_ERR_UNSUPPORTED
+
+
+def test_nonexistent_trailing_groups_never_touch_B():
+    # K/M = 14 groups: the last k-step of every tile has 2 padded groups, whose gathered rows are
+    # placeholders.  Whatever sits in B at the placeholder row (row 0) must not leak into C.
+    R, K, C, V, M = 64, 1400, 136, 32, 100
+    for seed in range(50):
+        A, mask, B = inputs.gen_problem(R, K, C, V, M, 1.0, seed=seed)
+        if not mask[:, 0].any():
+            break
+    else:
+        pytest.skip("no seed leaves column 0 unused")
+    Bh = B.view(np.float16).copy()
+    Bh[0, :] = np.inf
+    Bh[0, 1::2] = np.nan
+    h = compress_dev(A, mask, V, M)
+    ov, oc, om = o.compress(A, mask, V, M)
+    B0 = Bh.copy()
+    B0[0, :] = 0                                        # row 0 is not selected: the product ignores it
+    Cs, E = o.spmm_fp64(ov, oc, om, R, K, V, M, B0.view(np.uint16))
+    for v in variants_for(V):
+        for dt in (torch.float16, torch.float32):
+            out = binding.venom_spmm(h, torch.from_numpy(Bh).to(DEV), out_dtype=dt, variant=v)
+            assert bool(torch.isfinite(out).all()), binding.venom_spmm_variants()[v]
+            check(out, Cs, E)
