@@ -200,3 +200,31 @@ def test_nonexistent_trailing_groups_never_touch_B():
             out = binding.venom_spmm(h, torch.from_numpy(Bh).to(DEV), out_dtype=dt, variant=v)
             assert bool(torch.isfinite(out).all()), binding.venom_spmm_variants()[v]
             check(out, Cs, E)
+
+
+def test_product_replays_inside_a_captured_graph():
+    # venom_spmm allocates nothing and clears nothing, so it can be captured; every replay is
+    # compared with the eager result, with eager work and synchronisations in between.
+    R, K, C, V, M = 384, 1280, 520, 128, 32
+    A, mask, B = inputs.gen_problem(R, K, C, V, M, 1.0, seed=61)
+    h = compress_dev(A, mask, V, M)
+    B_d = to_dev_f16(B)
+    bias = torch.randn(R, device=DEV).half()
+    eager = binding.venom_spmm(h, B_d, bias=bias, activation="gelu")      # also the first-launch set-up
+    eager_plain = binding.venom_spmm(h, B_d)
+    out = torch.empty_like(eager)
+    out_plain = torch.empty_like(eager)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        binding.venom_spmm(h, B_d, out=out, bias=bias, activation="gelu")
+        binding.venom_spmm(h, B_d, out=out_plain)
+    for rep in range(4):
+        out.fill_(float("nan"))
+        out_plain.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager) and torch.equal(out_plain, eager_plain), rep
+        again = binding.venom_spmm(h, B_d)                                 # eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(again, eager_plain)
