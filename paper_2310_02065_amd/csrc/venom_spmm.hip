@@ -22,6 +22,7 @@
 //     store their output;
 //   * each XCD (one L2 each) walks a contiguous range of the column-tile-major tile list and keeps
 //     its slab of B hot.
+#include <atomic>
 #include <cstdio>
 #include <cstdlib>
 
@@ -60,6 +61,7 @@ struct SpmmParams {
 constexpr int kAbl = VENOM_ABLATE;   // experiment switches, fixed at compile time (never in the product library)
 #endif
 constexpr int kNumXcd = 8;
+constexpr int kMaxDevices = 16;      // devices whose per-device launch state is cached
 #ifndef VENOM_STAGES
 #define VENOM_STAGES 4
 #endif
@@ -715,10 +717,15 @@ venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, in
   p.per_xcd = (int)((total + kNumXcd - 1) / kNumXcd);
   // one resident workgroup per compute unit (two where the tile is small enough to share a unit);
   // each walks per_xcd / (grid / 8) tiles
-  int dev = 0, cus = 0;
-  if (hipGetDevice(&dev) != hipSuccess ||
-      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < kNumXcd)
-    return VENOM_ERR_HIP;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return VENOM_ERR_HIP;
+  static std::atomic<int> cu_count[kMaxDevices] = {};   // per device, filled on first use
+  int cus = (dev >= 0 && dev < kMaxDevices) ? cu_count[dev].load(std::memory_order_relaxed) : 0;
+  if (cus == 0) {
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < kNumXcd)
+      return VENOM_ERR_HIP;
+    if (dev >= 0 && dev < kMaxDevices) cu_count[dev].store(cus, std::memory_order_relaxed);
+  }
   const int share = (var.lds <= 80 * 1024 && var.threads <= 512) ? 2 : 1;
   const int64_t resident_per_xcd = (int64_t)(cus / kNumXcd) * share;
   const int64_t wg_per_xcd = p.per_xcd < resident_per_xcd ? p.per_xcd : resident_per_xcd;
@@ -729,12 +736,14 @@ venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, in
   auto fn = var.fn[c_dtype == 1 ? 1 : 0][epi];
   if (var.lds > 64 * 1024) {
     // opting in to more than 64 KB of dynamic LDS is a per-function attribute (set once per device)
-    static bool opted_in[kNumVariants][6][16] = {};
-    if (dev < 0 || dev >= 16 || !opted_in[variant][3 * c_dtype + epi][dev]) {
+    // (two threads racing here both set the same attribute: harmless)
+    static std::atomic<bool> opted_in[kNumVariants][6][kMaxDevices] = {};
+    const bool cached = dev >= 0 && dev < kMaxDevices;
+    if (!cached || !opted_in[variant][3 * c_dtype + epi][dev].load(std::memory_order_acquire)) {
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
                               var.lds) != hipSuccess)
         return VENOM_ERR_HIP;
-      if (dev >= 0 && dev < 16) opted_in[variant][3 * c_dtype + epi][dev] = true;
+      if (cached) opted_in[variant][3 * c_dtype + epi][dev].store(true, std::memory_order_release);
     }
   }
   const int launch_lds = var.lds;
