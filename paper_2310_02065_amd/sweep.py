@@ -4,6 +4,7 @@
 print a markdown table (useful TFLOP/s, speedup over dense, ideal speedup M/2).
 
     python -m paper_2310_02065_amd.sweep [--V 128] [--C 2048] [--M 4 8 16 32 64 128] [--iters 60]
+    python -m paper_2310_02065_amd.sweep --R 1024 --K 1024 4096 16384 --C 4096 --M 8 16 32   (a weight layer, varying K)
 """
 from __future__ import annotations
 
@@ -16,6 +17,8 @@ def main():
     ap.add_argument("--V", type=int, nargs="+", default=[128])
     ap.add_argument("--C", type=int, nargs="+", default=[2048])
     ap.add_argument("--M", type=int, nargs="+", default=[4, 8, 16, 32, 64, 128])
+    ap.add_argument("--R", type=int, default=None, help="rows of A (default: the sweep shape, 8192)")
+    ap.add_argument("--K", type=int, nargs="+", default=None, help="inner sizes (default: the sweep shape, 8192)")
     ap.add_argument("--iters", type=int, default=60)
     args = ap.parse_args()
 
@@ -28,7 +31,8 @@ def main():
         sys.exit(3)
     binding.lib()
     dev = torch.device("cuda:0")
-    R, K = inputs.SWEEP_SHAPE
+    R = args.R or inputs.SWEEP_SHAPE[0]
+    Ks = args.K or [inputs.SWEEP_SHAPE[1]]
 
     def timed(fn, iters):
         for _ in range(10):
@@ -41,9 +45,9 @@ def main():
         t = sorted(a.elapsed_time(b) for a, b in ev)
         return t[len(t) // 2]
 
-    print("| V | M | C | spmm ms | useful TFLOP/s | dense GEMM ms | speedup | ideal |")
-    print("|---|---|---|---|---|---|---|---|")
-    for C in args.C:
+    print("| R x K | V | M | C | spmm ms | useful TFLOP/s | dense GEMM ms | speedup | ideal |")
+    print("|---|---|---|---|---|---|---|---|---|")
+    for K, C in [(K, C) for K in Ks for C in args.C]:
         dense_ms = None
         for V in args.V:
             for M in args.M:
@@ -58,7 +62,7 @@ def main():
                     dense_ms = timed(lambda: torch.matmul(A_d, B_d, out=D), max(10, args.iters // 3))
                     del D
                 useful = 2.0 * R * C * K * 2 / M
-                print(f"| {V} | {M} | {C} | {ms:.4f} | {useful / ms * 1e-9:.0f} | {dense_ms:.4f} | {dense_ms / ms:.2f} | {M / 2:.0f} |",
+                print(f"| {R} x {K} | {V} | {M} | {C} | {ms:.4f} | {useful / ms * 1e-9:.0f} | {dense_ms:.4f} | {dense_ms / ms:.2f} | {M / 2:.0f} |",
                       flush=True)
                 h.close()
                 del A_d, B_d, out, h
