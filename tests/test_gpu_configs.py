@@ -44,6 +44,16 @@ def run_config(R, K, C, V, M, sigma, seed, sample_rows=None):
     got = out[torch.from_numpy(rows).to(DEV)].double().cpu().numpy()
     ok, info = o.accept(got, Cs, E)
     assert ok, info
+    # the fused epilogue and the token-major layer view at the same size, same sampled rows (= output features)
+    rng = np.random.default_rng(seed + 17)
+    bias = rng.standard_normal(R).astype(np.float16)
+    bias_d = torch.from_numpy(bias).to(DEV)
+    Ys, Ey = o.epilogue_fp64(Cs, E, bias.view(np.uint16)[rows], "gelu")
+    fused = binding.venom_spmm(h, B_d, bias=bias_d, activation="gelu")
+    ok, info2 = o.accept(fused[torch.from_numpy(rows).to(DEV)].double().cpu().numpy(), Ys, Ey)
+    assert ok, info2
+    layer = binding.venom_linear(h, B_d.t().contiguous(), bias=bias_d, activation="gelu")
+    assert torch.equal(layer, fused.t()), "token-major output differs from the transposed product"
     return info
 
 
