@@ -45,9 +45,9 @@ constexpr int kMaxM = 1024;
 
 __global__ void __launch_bounds__(256) compress_kernel(const uint16_t* __restrict__ A, int64_t lda,
                                                        const uint8_t* __restrict__ mask, int64_t ldm, int V, int M,
-                                                       int64_t G, int64_t W, uint32_t* __restrict__ values,
-                                                       uint16_t* __restrict__ columns, uint32_t* __restrict__ meta,
-                                                       unsigned long long* status) {
+                                                       int64_t G, int64_t W, int vec_ok,
+                                                       uint32_t* __restrict__ values, uint16_t* __restrict__ columns,
+                                                       uint32_t* __restrict__ meta, unsigned long long* status) {
   __shared__ uint8_t used[kStepGroups][kMaxM];
   __shared__ int sel[kStepGroups][kSelCols];
   __shared__ int cols_ok[kStepGroups];
@@ -59,8 +59,26 @@ __global__ void __launch_bounds__(256) compress_kernel(const uint16_t* __restric
 
   for (int i = tid; i < kStepGroups * M; i += blockDim.x) used[i / M][i % M] = 0;
   __syncthreads();
-  for (int64_t i = tid; i < (int64_t)V * span; i += blockDim.x) {
-    const int v = (int)(i / span), c = (int)(i % span);
+  // a thread owns 8 neighbouring columns (one 8-byte mask load per row) and a slice of the rows;
+  // columns past the last multiple of 8 and unaligned masks take the byte loop
+  const int units = vec_ok ? span / 8 : 0;
+  if (units > 0) {
+    const int slices = blockDim.x / units > 0 ? blockDim.x / units : 1;
+    for (int u0 = 0; u0 < units; u0 += blockDim.x) {
+      const int u = u0 + (slices > 1 ? tid % units : tid);
+      const int slice = slices > 1 ? tid / units : 0;
+      if (u < units && slice < slices) {
+        unsigned long long seen = 0;               // OR of the 8 mask bytes over this thread's rows
+        for (int v = slice; v < V; v += slices)
+          seen |= *reinterpret_cast<const unsigned long long*>(mask + (b * V + v) * ldm + g0 * M + 8 * u);
+        for (int e = 0; e < 8; ++e)
+          if ((seen >> (8 * e)) & 0xffull) { const int c = 8 * u + e; used[c / M][c % M] = 1; }
+      }
+    }
+  }
+  const int tail0 = units * 8, tail = span - tail0;
+  for (int64_t i = tid; i < (int64_t)V * tail; i += blockDim.x) {
+    const int v = (int)(i / tail), c = tail0 + (int)(i % tail);
     if (mask[(b * V + v) * ldm + g0 * M + c]) used[c / M][c % M] = 1;  // benign: every writer stores 1
   }
   __syncthreads();
@@ -84,10 +102,13 @@ __global__ void __launch_bounds__(256) compress_kernel(const uint16_t* __restric
     }
   }
   __syncthreads();
-  for (int v = tid; v < V; v += blockDim.x) {
-    const int64_t r = b * V + v;
-    uint32_t word = 0;
-    for (int t = 0; t < ng; ++t) {
+  // one thread per (row, group): eight neighbouring lanes hold the eight nibbles of a metadata word
+  // and combine them with three lane exchanges
+  for (int i = tid; i < ((V * 8 + 255) / 256) * 256; i += blockDim.x) {
+    const int v = i >> 3, t = i & 7;
+    uint32_t nib = 0;
+    if (v < V && t < ng) {
+      const int64_t r = b * V + v;
       const int64_t base = g0 + t;
       const uint8_t* mrow = mask + r * ldm + base * M;
       int kept[kSelCols], nk = 0;
@@ -108,9 +129,12 @@ __global__ void __launch_bounds__(256) compress_kernel(const uint16_t* __restric
       const uint32_t v0 = k0 ? arow[sel[t][p0]] : 0u;
       const uint32_t v1 = k1 ? arow[sel[t][p1]] : 0u;
       values[r * G + base] = v0 | (v1 << 16);
-      word |= (uint32_t)(p0 | (p1 << 2)) << (4 * t);
+      nib = (uint32_t)(p0 | (p1 << 2)) << (4 * t);
     }
-    meta[r * W + w] = word;
+    nib |= __shfl_xor(nib, 1);
+    nib |= __shfl_xor(nib, 2);
+    nib |= __shfl_xor(nib, 4);
+    if (v < V && t == 0) meta[(b * V + v) * W + w] = nib;
   }
 }
 
@@ -209,7 +233,9 @@ hipError_t launch_compress(const uint16_t* A, int64_t lda, const uint8_t* mask, 
   if (e != hipSuccess) return e;
   if (L.R > 0 && L.G > 0) {
     dim3 grid((unsigned)L.W, (unsigned)L.Rb);
-    hipLaunchKernelGGL(compress_kernel, grid, dim3(256), 0, st, A, lda, mask, ldm, h.V, h.M, L.G, L.W,
+    // wide mask loads need every 8-group chunk of every row to start on an 8-byte boundary
+    const int vec_ok = ldm % 8 == 0 && reinterpret_cast<uintptr_t>(mask) % 8 == 0;
+    hipLaunchKernelGGL(compress_kernel, grid, dim3(256), 0, st, A, lda, mask, ldm, h.V, h.M, L.G, L.W, vec_ok,
                        reinterpret_cast<uint32_t*>(h.ws + L.off_values),
                        reinterpret_cast<uint16_t*>(h.ws + L.off_columns),
                        reinterpret_cast<uint32_t*>(h.ws + L.off_meta), status);

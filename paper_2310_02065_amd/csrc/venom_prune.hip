@@ -27,15 +27,25 @@ __global__ void zero_u64_kernel(unsigned long long* a, unsigned long long* b, in
   }
 }
 
+// Ordering key of a magnitude that fits 16 bits: |bits|, with every non-finite value mapped to
+// the one key above all finite ones (same order as magnitude_units, ties included).
+__device__ __forceinline__ unsigned magnitude_key(uint16_t bits) {
+  const unsigned a = bits & 0x7fffu;
+  return a > 0x7c00u ? 0x7c00u : a;
+}
+
 // One workgroup per (block row b, chunk of `gpw` groups): V rows x gpw*M columns.
-//   phase 1: column masses into LDS (64-bit integer adds), the block's total mass
+//   phase 1: column masses into LDS (64-bit integer adds), the block's total mass, mask zero fill.
+//            A thread owns 8 neighbouring columns (one 16-byte load, one 8-byte mask store) and a
+//            slice of the rows, sums in registers and adds once per column; columns past the last
+//            multiple of 8 and unaligned inputs take the element-wise loop.
 //   phase 2: one thread per group picks the 4 columns: largest mass first, smaller index on ties,
 //            then sorted ascending
 //   phase 3: one thread per (row, group): the 2 largest magnitudes among the 4, smaller position on
-//            ties; the mask segment is zero-filled first, then the kept positions are set
+//            ties; sets the two mask bytes
 __global__ void __launch_bounds__(256) prune_kernel(const uint16_t* __restrict__ A, int64_t lda, int V, int M,
-                                                    int64_t G, int gpw, uint8_t* __restrict__ mask, int64_t ldm,
-                                                    unsigned long long* __restrict__ kept_mass,
+                                                    int64_t G, int gpw, int vec_ok, uint8_t* __restrict__ mask,
+                                                    int64_t ldm, unsigned long long* __restrict__ kept_mass,
                                                     unsigned long long* __restrict__ total_mass) {
   __shared__ unsigned long long mass[kPruneMaxCols];
   __shared__ int sel[kPruneMaxCols / kSelCols][kSelCols];
@@ -50,8 +60,36 @@ __global__ void __launch_bounds__(256) prune_kernel(const uint16_t* __restrict__
   if (tid == 0) { wg_total = 0; wg_kept = 0; }
   __syncthreads();
   unsigned long long my_total = 0;
-  for (int64_t i = tid; i < (int64_t)V * span; i += blockDim.x) {
-    const int v = (int)(i / span), c = (int)(i % span);
+  const int units = vec_ok ? span / 8 : 0;         // 8-column units handled with wide accesses
+  if (units > 0) {
+    const int slices = blockDim.x / units > 0 ? blockDim.x / units : 1;   // row slices working side by side
+    for (int u0 = 0; u0 < units; u0 += blockDim.x) {                        // (more than 256 units: several sweeps)
+      const int u = u0 + (slices > 1 ? tid % units : tid);
+      const int slice = slices > 1 ? tid / units : 0;
+      if (u < units && slice < slices) {
+        unsigned long long m8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        for (int v = slice; v < V; v += slices) {
+          const uint4 w = *reinterpret_cast<const uint4*>(A + (b * V + v) * lda + g0 * M + 8 * u);
+          const uint32_t ws[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            m8[2 * e] += magnitude_units((uint16_t)ws[e]);
+            m8[2 * e + 1] += magnitude_units((uint16_t)(ws[e] >> 16));
+          }
+          *reinterpret_cast<uint2*>(mask + (b * V + v) * ldm + g0 * M + 8 * u) = make_uint2(0, 0);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          if (m8[e]) atomicAdd(&mass[8 * u + e], m8[e]);
+          my_total += m8[e];
+        }
+      }
+    }
+  }
+  const int tail0 = units * 8;                     // columns not covered above
+  const int tail = span - tail0;
+  for (int64_t i = tid; i < (int64_t)V * tail; i += blockDim.x) {
+    const int v = (int)(i / tail), c = tail0 + (int)(i % tail);
     const unsigned long long m = magnitude_units(A[(b * V + v) * lda + g0 * M + c]);
     mask[(b * V + v) * ldm + g0 * M + c] = 0;
     if (m) atomicAdd(&mass[c], m);
@@ -80,16 +118,17 @@ __global__ void __launch_bounds__(256) prune_kernel(const uint16_t* __restrict__
   for (int i = tid; i < V * ng; i += blockDim.x) {
     const int v = i / ng, t = i % ng;
     const int64_t base = (b * V + v) * lda + (g0 + t) * M;
-    unsigned long long m[kSelCols];
-    for (int p = 0; p < kSelCols; ++p) m[p] = magnitude_units(A[base + sel[t][p]]);
+    uint16_t w[kSelCols];
+    unsigned key[kSelCols];
+    for (int p = 0; p < kSelCols; ++p) { w[p] = A[base + sel[t][p]]; key[p] = magnitude_key(w[p]); }
     int p0 = 0;
-    for (int p = 1; p < kSelCols; ++p) if (m[p] > m[p0]) p0 = p;
+    for (int p = 1; p < kSelCols; ++p) if (key[p] > key[p0]) p0 = p;
     int p1 = p0 == 0 ? 1 : 0;
-    for (int p = 0; p < kSelCols; ++p) if (p != p0 && m[p] > m[p1]) p1 = p;
+    for (int p = 0; p < kSelCols; ++p) if (p != p0 && key[p] > key[p1]) p1 = p;
     uint8_t* mrow = mask + (b * V + v) * ldm + (g0 + t) * M;
     mrow[sel[t][p0]] = 1;
     mrow[sel[t][p1]] = 1;
-    my_kept += m[p0] + m[p1];
+    my_kept += magnitude_units(w[p0]) + magnitude_units(w[p1]);
   }
   if (my_kept) atomicAdd(&wg_kept, my_kept);
   __syncthreads();
@@ -109,8 +148,11 @@ hipError_t launch_prune(const uint16_t* A, int64_t lda, int64_t R, int64_t K, in
   if (gpw > kStepGroups) gpw = kStepGroups;
   if (gpw < 1) gpw = 1;
   const int64_t chunks = (G + gpw - 1) / gpw;
-  hipLaunchKernelGGL(prune_kernel, dim3((unsigned)chunks, (unsigned)Rb), dim3(256), 0, st, A, lda, V, M, G, gpw, mask, ldm,
-                     kept_mass, total_mass);
+  // wide accesses need every chunk of every row to start on a 16-byte (A) / 8-byte (mask) boundary
+  const int vec_ok = ((int64_t)gpw * M) % 8 == 0 && lda % 8 == 0 && ldm % 8 == 0 &&
+                     reinterpret_cast<uintptr_t>(A) % 16 == 0 && reinterpret_cast<uintptr_t>(mask) % 8 == 0;
+  hipLaunchKernelGGL(prune_kernel, dim3((unsigned)chunks, (unsigned)Rb), dim3(256), 0, st, A, lda, V, M, G, gpw, vec_ok,
+                     mask, ldm, kept_mass, total_mass);
   return hipGetLastError();
 }
 
