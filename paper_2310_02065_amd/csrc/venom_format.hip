@@ -151,19 +151,16 @@ __global__ void __launch_bounds__(256) pack_rowidx_kernel(const uint16_t* __rest
 }
 
 // canonical -> the kernel's packed A stream.  One record per (block row, k-step):
-//   [V/32 tiles x 1024 B of values][1024 B tail]
+//   [V/32 tiles x 1024 B of values][512 B tail]
 // values of a tile: 64 lanes x 8 halfs; lane = 32*h + i holds row 32*tile + i and the two kept
 // values of groups 8*step + 4*h .. +3 -- the A operand of v_smfmac_f32_32x32x32_f16.
-// tail: bytes [0, 512): 64 lanes x 4 x uint16, entry [lane][tile] = the lane's four canonical nibbles
-//       for that tile (a lane reads its 8 bytes with one LDS load; the matrix instruction picks
-//       the 16-bit field with its ABID operand); bytes [512, 640): the 32 B-row ids of k-step
-//       step + kRidLead (0 past the end), so the gather addresses travel with the stream;
-//       the rest is zero.
-// One thread per lane-slot: (block row, step, tile, lane) for tile < vt; tile == vt writes the
-// row ids and the padding.
+// tail: 64 lanes x 4 x uint16, entry [lane][tile] = the lane's four canonical nibbles for that tile
+//       (a lane reads its 8 bytes with one LDS load; the matrix instruction picks the 16-bit field
+//       with its ABID operand).
+// One thread per lane-slot: (block row, step, tile, lane) for tile < vt; tile == vt clears the
+// index words of the tiles that do not exist.
 __global__ void __launch_bounds__(256) pack_arec_kernel(const uint32_t* __restrict__ values,
-                                                        const uint32_t* __restrict__ meta,
-                                                        const int32_t* __restrict__ rowidx, int64_t G, int64_t W,
+                                                        const uint32_t* __restrict__ meta, int64_t G, int64_t W,
                                                         int64_t steps, int vt, int V, int64_t total,
                                                         char* __restrict__ arec) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -174,15 +171,7 @@ __global__ void __launch_bounds__(256) pack_arec_kernel(const uint32_t* __restri
   char* rec = arec + (b * steps + s) * ((int64_t)vt * kTileValBytes + kTailBytes);
   char* tail = rec + vt * kTileValBytes;
   if (tile == vt) {
-    // row ids of step s + kRidLead, then zero padding (2 dwords per lane cover bytes 512..1023)
-    uint32_t* w = reinterpret_cast<uint32_t*>(tail + kTailRidOff);
-    for (int k = lane; k < (kTailBytes - kTailRidOff) / 4; k += 64) {
-      uint32_t v = 0;
-      if (k < kStepRows && s + kRidLead < steps) v = (uint32_t)rowidx[(b * steps + s + kRidLead) * kStepRows + k];
-      w[k] = v;
-    }
-    if (vt < kMaxTiles)   // unused tile slots of the index words
-      for (int t = vt; t < kMaxTiles; ++t) reinterpret_cast<uint16_t*>(tail)[lane * kMaxTiles + t] = 0;
+    for (int t = vt; t < kMaxTiles; ++t) reinterpret_cast<uint16_t*>(tail)[lane * kMaxTiles + t] = 0;
     return;
   }
   const int64_t r = b * V + tile * kTileRows + (lane % 32);
@@ -210,11 +199,7 @@ __global__ void __launch_bounds__(256) decompress_kernel(const char* __restrict_
   const char* rec = arec + (b * steps + s) * ((int64_t)vt * kTileValBytes + kTailBytes);
   const uint32_t word = reinterpret_cast<const uint16_t*>(rec + vt * kTileValBytes)[lane * kMaxTiles + tile];
   const uint32_t nib = (word >> (4 * ge)) & 0xfu;
-  // row ids: from the stream when an earlier record carries them, else from the row-id array
-  const int32_t* ri = (s >= kRidLead)
-      ? reinterpret_cast<const int32_t*>(arec + (b * steps + s - kRidLead) * ((int64_t)vt * kTileValBytes + kTailBytes) +
-                                         vt * kTileValBytes + kTailRidOff) + 4 * t
-      : rowidx + (b * steps + s) * kStepRows + 4 * t;
+  const int32_t* ri = rowidx + (b * steps + s) * kStepRows + 4 * t;
   const uint16_t* pv = reinterpret_cast<const uint16_t*>(rec + tile * kTileValBytes) + lane * 8 + 2 * ge;
   uint16_t out = 0;
   if (ri[nib & 3] == k) out = pv[0];
@@ -254,8 +239,7 @@ hipError_t launch_pack(const venom_handle& h, hipStream_t st) {
   total = L.Rb * L.steps * (L.vt + 1) * 64;
   hipLaunchKernelGGL(pack_arec_kernel, dim3(blocks_for(total)), dim3(256), 0, st,
                      reinterpret_cast<const uint32_t*>(h.ws + L.off_values),
-                     reinterpret_cast<const uint32_t*>(h.ws + L.off_meta),
-                     reinterpret_cast<const int32_t*>(h.ws + L.off_rowidx), L.G, L.W, L.steps, L.vt, h.V, total,
+                     reinterpret_cast<const uint32_t*>(h.ws + L.off_meta), L.G, L.W, L.steps, L.vt, h.V, total,
                      h.ws + L.off_arec);
   return hipGetLastError();
 }

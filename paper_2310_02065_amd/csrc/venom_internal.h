@@ -15,9 +15,7 @@ constexpr int kStepGroups = 8; // groups of M columns consumed per k-step: 8 gro
 constexpr int kStepRows = kStepGroups * kSelCols;  // gathered rows of B per k-step
 constexpr int kTileValBytes = 1024;                // packed values of one 32-row tile for one k-step
 constexpr int kMaxTiles = 4;                       // the product kernel serves V = 32, 64, 96, 128
-constexpr int kTailBytes = 1024;                   // record tail: index words (512 B), row ids (128 B), padding
-constexpr int kTailRidOff = 512;                   // byte offset of the row ids inside the tail
-constexpr int kRidLead = 3;                        // the tail of record u names the B rows of k-step u + kRidLead
+constexpr int kTailBytes = 512;                    // record tail: the index words, 64 lanes x 4 tiles x 16 bits
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

@@ -228,7 +228,9 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
       {
         const uint32_t dst = lds0 + ARING + a_slot * A_BYTES;
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) dma16(a_ptr + j * 1024, lane_off, dst + j * 1024);
+        for (int j = 0; j < VT; ++j) dma16(a_ptr + j * 1024, lane_off, dst + j * 1024);
+        if (lane < kTailBytes / 16) dma16(a_ptr + T_OFF, lane_off, dst + T_OFF);   // the 512-byte tail: half a wave
+
       }
       a_ptr += p.rec_bytes;
       a_slot = a_slot + 1 == NA ? 0 : a_slot + 1;
