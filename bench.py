@@ -31,7 +31,7 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/),
 # scaled by the same counters read on a plain copy kernel; None where not measured yet.
-MEASURED_TRAFFIC_BYTES = {"gpt3": 1287534336}   # 1086.2 MB read + 201.3 MB written
+MEASURED_TRAFFIC_BYTES = {"gpt3": 1125849804}   # 924.5 MB read + 201.3 MB written
 
 
 def algorithmic_bytes(R, K, C, V, M, out_bytes=2):

@@ -48,6 +48,8 @@ struct SpmmParams {
   int nbr, nct;            // block rows, column tiles
   int per_xcd;             // ceil(nbr*nct / 8)
   int stream_out;          // nonzero: non-temporal stores of C
+  int serpentine;          // nonzero: a workgroup's odd tiles run their k-steps backwards, so the end of the
+                           // slab of B that the last tile left in L2 is where the next one starts
   int pad_row0;            // first gathered row of a tile's LAST k-step that lies past the end of K (32: none)
   const _Float16* bias;    // one entry per row of C, or null
   int act;                 // venom_activation_t
@@ -64,6 +66,9 @@ constexpr int kNumXcd = 8;
 constexpr int kMaxDevices = 16;      // devices whose per-device launch state is cached
 #ifndef VENOM_STAGES
 #define VENOM_STAGES 4
+#endif
+#ifndef VENOM_NA512
+#define VENOM_NA512 6
 #endif
 constexpr int kStages = VENOM_STAGES;           // B ring depth: three k-steps are in flight
 constexpr int kRidSlots = 16;        // row-id ring: 128 bytes per k-step
@@ -221,6 +226,7 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
     int a_t = 0, a_s = 0, a_slot = 0;
     tw.locate(p, 0, ct, br);
     const char* a_ptr = p.arec + (int64_t)br * p.steps * p.rec_bytes;
+    int64_t a_inc = p.rec_bytes;
     auto next_record = [&]() {
 #ifdef VENOM_ABLATE
       if (!(kAbl & (8 | 1024)))
@@ -232,29 +238,35 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
         if (lane < kTailBytes / 16) dma16(a_ptr + T_OFF, lane_off, dst + T_OFF);   // the 512-byte tail: half a wave
 
       }
-      a_ptr += p.rec_bytes;
+      a_ptr += a_inc;
       a_slot = a_slot + 1 == NA ? 0 : a_slot + 1;
       if (++a_s == p.steps) {
         a_s = 0;
         if (++a_t < tw.count) {
           tw.locate(p, a_t, ct, br);
-          a_ptr = p.arec + (int64_t)br * p.steps * p.rec_bytes;
+          const bool back = p.serpentine && (a_t & 1);       // odd tiles run their k-steps backwards
+          a_inc = back ? -p.rec_bytes : p.rec_bytes;
+          a_ptr = p.arec + ((int64_t)br * p.steps + (back ? p.steps - 1 : 0)) * p.rec_bytes;
         }
       }
     };
     // row-id stream position
     int r_t = 0, r_s = 0, r_slot = 0;
     const char* r_ptr = reinterpret_cast<const char*>(p.rowidx) + (int64_t)br * p.steps * (kStepRows * 4);
+    int r_inc = kStepRows * 4;
     auto next_rowids = [&]() {
       if (lane < kStepRows) dma4(r_ptr, lane * 4, lds0 + RIDRING + r_slot * (kStepRows * 4));
-      r_ptr += kStepRows * 4;
+      r_ptr += r_inc;
       r_slot = (r_slot + 1) % kRidSlots;
       if (++r_s == p.steps) {
         r_s = 0;
         if (++r_t < tw.count) {
           int ct2, br2;
           tw.locate(p, r_t, ct2, br2);
-          r_ptr = reinterpret_cast<const char*>(p.rowidx) + (int64_t)br2 * p.steps * (kStepRows * 4);
+          const bool back = p.serpentine && (r_t & 1);
+          r_inc = back ? -(kStepRows * 4) : kStepRows * 4;
+          r_ptr = reinterpret_cast<const char*>(p.rowidx) +
+                  ((int64_t)br2 * p.steps + (back ? p.steps - 1 : 0)) * (kStepRows * 4);
         }
       }
     };
@@ -350,12 +362,12 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
     barrier_only();                                // the first row ids are on chip
     for (int j = 0; j < PB && j < G; ++j) issue(rowids_of(j));
     int ridv = PB < G ? rowids_of(PB) : 0;         // row ids of the k-step issued next
-    int c_s = 0;
+    int c_s = 0, c_t = 0;                          // k-step inside the tile / tile the consumers are on
     for (int g = 0; g < G; ++g) {
       // this producer's part of k-step g has landed when at most its loads of the later steps
       // (up to two) are pending
       const int left = G - 1 - g;
-      if (p.pad_row0 < kStepRows && c_s == p.steps - 1) {
+      if (p.pad_row0 < kStepRows && c_s == ((p.serpentine && (c_t & 1)) ? 0 : p.steps - 1)) {
         // The last k-step of a tile when K/M is not a multiple of 8: its trailing groups do not
         // exist.  Their values are zero, but 0 x Inf is not, so the rows gathered for them (row 0
         // of B, a valid address that keeps the load count exact) are overwritten with zeros once
@@ -375,7 +387,7 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
         issue(ridv);
         if (g + PB + 1 < G) ridv = rowids_of(g + PB + 1);
       }
-      if (++c_s == p.steps) { c_s = 0; barrier_only(); }
+      if (++c_s == p.steps) { c_s = 0; ++c_t; barrier_only(); }
     }
   } else {
     // ========================================================================= consumers
@@ -654,7 +666,7 @@ constexpr int lds_bytes() {   // B ring, A ring, row-id ring (the output staging
         spmm_kernel<VT, NC, NPB, NA, true, 2> } } }
 
 static const Variant kVariants[] = {
-    VARIANT("v128_c512", 4, 8, 3, 6), VARIANT("v128_c256", 4, 4, 2, 9), VARIANT("v128_c128", 4, 2, 1, 10),
+    VARIANT("v128_c512", 4, 8, 3, VENOM_NA512), VARIANT("v128_c256", 4, 4, 2, 9), VARIANT("v128_c128", 4, 2, 1, 10),
     VARIANT("v96_c512", 3, 8, 3, 7),  VARIANT("v96_c256", 3, 4, 2, 10), VARIANT("v96_c128", 3, 2, 1, 10),
     VARIANT("v64_c512", 2, 8, 3, 10), VARIANT("v64_c256", 2, 4, 2, 10), VARIANT("v64_c128", 2, 2, 1, 10),
     VARIANT("v32_c512", 1, 8, 3, 10), VARIANT("v32_c256", 1, 4, 2, 10), VARIANT("v32_c128", 1, 2, 1, 10),
@@ -704,6 +716,11 @@ venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, in
   p.steps = (int)L.steps;
   p.bias = reinterpret_cast<const _Float16*>(bias);
   p.act = act;
+#ifdef VENOM_NO_SERPENTINE
+  p.serpentine = 0;
+#else
+  p.serpentine = 1;
+#endif
   p.pad_row0 = (L.G % kStepGroups) ? (int)(L.G % kStepGroups) * kSelCols : kStepRows;
   p.stream_out = L.steps >= 32;   // measured: +3 % at 48 k-steps per tile, -20 % at 8
 #ifdef VENOM_ABLATE
