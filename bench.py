@@ -31,7 +31,12 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/),
 # scaled by the same counters read on a plain copy kernel; None where not measured yet.
-MEASURED_TRAFFIC_BYTES = {"gpt3": 1125849804}   # 924.5 MB read + 201.3 MB written
+MEASURED_TRAFFIC_BYTES = {
+    "gpt3": 1125849804,                    # 924.5 MB read + 201.3 MB written
+    "bert_large": 187424768,               # 53.2 MB read + 134.2 MB written
+    "sweep_v128_m128_c2048": 86499328,     # 52.9 MB read + 33.6 MB written
+    "sweep_v128_m32_c256": 36153344,       # 32.0 MB read + 4.2 MB written
+}
 
 
 def algorithmic_bytes(R, K, C, V, M, out_bytes=2):
@@ -45,7 +50,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="gpt3", help="gpt3 | bert_large | bert_base | tiny")
+    ap.add_argument("--workload", default="gpt3", help="gpt3 | bert_large | bert_base | tiny | sweep_v{V}_m{M}_c{C}")
     ap.add_argument("--variant", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
@@ -70,9 +75,17 @@ def main():
     torch.cuda.set_device(dev)
 
     names = list(inputs.CONFIGS)
-    R, K, C, V, M, sigma = inputs.CONFIGS[args.workload]
+    if args.workload in inputs.CONFIGS:
+        R, K, C, V, M, sigma = inputs.CONFIGS[args.workload]
+        seed = inputs.config_seed(names.index(args.workload))
+    else:
+        # a point of the sparsity sweep: "sweep_v{V}_m{M}_c{C}", e.g. sweep_v128_m32_c256 (bandwidth-bound)
+        parts = dict((p[0], int(p[1:])) for p in args.workload.split("_")[1:])
+        V, M, C = parts["v"], parts["m"], parts["c"]
+        R, K = inputs.SWEEP_SHAPE
+        sigma = 1.0
+        seed = inputs.config_seed(4) + 7 * M + V + C
     N = 2
-    seed = inputs.config_seed(names.index(args.workload))
     t0 = time.time()
     A_bits, mask, B_bits = inputs.gen_problem(R, K, C, V, M, sigma, seed=seed)
     t_gen = time.time() - t0
