@@ -228,3 +228,26 @@ def test_product_replays_inside_a_captured_graph():
         again = binding.venom_spmm(h, B_d)                                 # eager work between replays
         torch.cuda.synchronize()
         assert torch.equal(again, eager_plain)
+
+
+def test_runs_on_the_stream_it_is_given():
+    R, K, C, V, M = 256, 512, 264, 128, 16
+    A, mask, B = inputs.gen_problem(R, K, C, V, M, 1.0, seed=71)
+    side = torch.cuda.Stream()                       # default priority
+    B_d = to_dev_f16(B)
+    A_d = to_dev_f16(A)
+    m_d = torch.from_numpy(mask).to(DEV)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        h = binding.venom_compress(A_d, m_d, V, 2, M)          # uses the current (side) stream
+        out = binding.venom_spmm(h, B_d)
+        gate = torch.cuda.Event()
+        gate.record(side)
+    # an explicit stream argument, while another stream is current
+    out2 = torch.empty_like(out)
+    binding.venom_spmm(h, B_d, out=out2, stream=side)
+    side.synchronize()
+    ov, oc, om = o.compress(A, mask, V, M)
+    Cs, E = o.spmm_fp64(ov, oc, om, R, K, V, M, B)
+    check(out, Cs, E)
+    assert torch.equal(out, out2)
