@@ -158,29 +158,38 @@ struct TileWalk {
 
 // MODE 0: the plain product; 1: fused bias / activation; 2: the same with C written transposed
 // (token-major).  Separate instantiations: the plain kernel carries none of the epilogue code.
-template <int VT, int NC, int NPB, int NA, bool OUT_F32, int MODE>
+// PAIR 2: the workgroup owns TWO neighbouring block rows and half the columns per wave.  Legal only
+// where both block rows select the same columns of every group (always at M = 4, where all four are
+// selected): the gathered rows of B then serve 2V rows, which halves the gather per matrix
+// instruction, the kernel's tightest resource.
+template <int VT, int NC, int NPB, int NA, bool OUT_F32, int MODE, int PAIR>
 __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams p) {
   static_assert(NC == 2 || NC == 4 || NC == 8, "consumer waves per workgroup");
+  static_assert(PAIR == 1 || PAIR == 2, "block rows per workgroup");
   constexpr bool EPI = MODE != 0;
   static_assert(VT >= 1 && VT <= kMaxTiles, "32-row tiles per block row");
   static_assert(NA >= 4, "the A ring holds the record being read, the next one, and records in flight");
-  constexpr int BSC = 64 * NC;                     // columns of C per workgroup
+  constexpr int RT = PAIR * VT;                    // 32-row tiles a consumer wave accumulates
+  constexpr int CT = 2 / PAIR;                     // 32-column tiles a consumer wave accumulates
+  constexpr int WCOLS = 32 * CT;                   // columns of C per consumer wave
+  constexpr int BSC = WCOLS * NC;                  // columns of C per workgroup
   constexpr int ROW_BYTES = 2 * BSC;               // one gathered row of B in LDS
   constexpr int RPI = 1024 / ROW_BYTES;            // rows written by one wave-wide 16-byte load
   constexpr int LPR = 64 / RPI;                    // lanes (= 16-byte slots) per row
   constexpr int NI = kStepRows / RPI;              // B loads per k-step (4 * NC)
   constexpr int NBH = (NI + NPB - 1) / NPB, NBL = NI / NPB, NBHI = NI % NPB;  // ... per B producer
   constexpr int B_BYTES = kStepRows * ROW_BYTES;
-  constexpr int A_BYTES = VT * kTileValBytes + kTailBytes;   // one A record
+  constexpr int REC = VT * kTileValBytes + kTailBytes;       // one A record
+  constexpr int A_BYTES = PAIR * REC;              // the records of one k-step (one per block row)
   constexpr int T_OFF = VT * kTileValBytes;        // record tail: index words
   constexpr int ARING = kStages * B_BYTES;         // LDS: [B ring][A ring][row-id ring]
   constexpr int RIDRING = ARING + NA * A_BYTES;
-  constexpr int NJ = VT + 1;                       // A loads per k-step: VT value blocks + the tail
+  constexpr int NJ = PAIR * (VT + 1);              // A loads per k-step: VT value blocks + the tail, per block row
   constexpr int PA = NA - 2;                       // k-steps the A stream runs ahead (a record stays one step
                                                    // longer than its k-step: the late consumers re-read it)
   constexpr int PB = kStages - 1;                  // k-steps the B stream runs ahead
   static_assert((kStages - 2) * NBH <= 63 && PA * NJ <= 63, "load counts fit the 6-bit counter");
-  static_assert(NC * 4096 <= B_BYTES, "the output staging of all consumers fits one B stage");
+  static_assert(NC * 32 * WCOLS * 2 <= B_BYTES, "the output staging of all consumers fits one B stage");
   constexpr int RA = PA + PB + 1;                  // k-steps the row-id stream runs ahead: the ids of step
                                                    // g+PB+1 are then older than record g+1 in the load queue
   static_assert(kRidSlots >= RA - PB + 2, "a row-id slot is rewritten only after its last reader");
@@ -225,7 +234,10 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
     // record stream position
     int a_t = 0, a_s = 0, a_slot = 0;
     tw.locate(p, 0, ct, br);
-    const char* a_ptr = p.arec + (int64_t)br * p.steps * p.rec_bytes;
+    // (br numbers groups of PAIR block rows; the records of the second block row of a pair lie
+    // pair_gap bytes after those of the first)
+    const char* a_ptr = p.arec + (int64_t)br * PAIR * p.steps * p.rec_bytes;
+    const int64_t pair_gap = (int64_t)p.steps * p.rec_bytes;
     int64_t a_inc = p.rec_bytes;
     auto next_record = [&]() {
 #ifdef VENOM_ABLATE
@@ -234,9 +246,12 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
       {
         const uint32_t dst = lds0 + ARING + a_slot * A_BYTES;
 #pragma unroll
-        for (int j = 0; j < VT; ++j) dma16(a_ptr + j * 1024, lane_off, dst + j * 1024);
-        if (lane < kTailBytes / 16) dma16(a_ptr + T_OFF, lane_off, dst + T_OFF);   // the 512-byte tail: half a wave
-
+        for (int pr = 0; pr < PAIR; ++pr) {
+          const char* src = a_ptr + pr * pair_gap;
+#pragma unroll
+          for (int j = 0; j < VT; ++j) dma16(src + j * 1024, lane_off, dst + pr * REC + j * 1024);
+          if (lane < kTailBytes / 16) dma16(src + T_OFF, lane_off, dst + pr * REC + T_OFF);   // the 512-byte tail: half a wave
+        }
       }
       a_ptr += a_inc;
       a_slot = a_slot + 1 == NA ? 0 : a_slot + 1;
@@ -246,13 +261,13 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
           tw.locate(p, a_t, ct, br);
           const bool back = p.serpentine && (a_t & 1);       // odd tiles run their k-steps backwards
           a_inc = back ? -p.rec_bytes : p.rec_bytes;
-          a_ptr = p.arec + ((int64_t)br * p.steps + (back ? p.steps - 1 : 0)) * p.rec_bytes;
+          a_ptr = p.arec + ((int64_t)br * PAIR * p.steps + (back ? p.steps - 1 : 0)) * p.rec_bytes;
         }
       }
     };
     // row-id stream position
     int r_t = 0, r_s = 0, r_slot = 0;
-    const char* r_ptr = reinterpret_cast<const char*>(p.rowidx) + (int64_t)br * p.steps * (kStepRows * 4);
+    const char* r_ptr = reinterpret_cast<const char*>(p.rowidx) + (int64_t)br * PAIR * p.steps * (kStepRows * 4);
     int r_inc = kStepRows * 4;
     auto next_rowids = [&]() {
       if (lane < kStepRows) dma4(r_ptr, lane * 4, lds0 + RIDRING + r_slot * (kStepRows * 4));
@@ -266,7 +281,7 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
           const bool back = p.serpentine && (r_t & 1);
           r_inc = back ? -(kStepRows * 4) : kStepRows * 4;
           r_ptr = reinterpret_cast<const char*>(p.rowidx) +
-                  ((int64_t)br2 * p.steps + (back ? p.steps - 1 : 0)) * (kStepRows * 4);
+                  ((int64_t)br2 * PAIR * p.steps + (back ? p.steps - 1 : 0)) * (kStepRows * 4);
         }
       }
     };
@@ -394,53 +409,56 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
     // Transposing LDS reads that build the B operand.  Sub-read cb of a 32-column tile: lane block
     // blk = lane/16 reads group t = 4*(cb/2) + 2*(blk/2) + cb%2, 16-column window 2*tile + blk%2;
     // inside the block lane i reads row 4*t + i/4, 8-byte piece i%4.
-    int rd_off[2][4];
+    int rd_off[CT][4];
     {
       const int blk = lane >> 4, i = lane & 15, e = i >> 2, c8 = i & 3;
 #pragma unroll
-      for (int tc = 0; tc < 2; ++tc)
+      for (int tc = 0; tc < CT; ++tc)
 #pragma unroll
         for (int cb = 0; cb < 4; ++cb) {
           const int t = 4 * (cb >> 1) + 2 * (blk >> 1) + (cb & 1);
           const int rho = 4 * t + e;
-          const int win = wave * 4 + tc * 2 + (blk & 1);
+          const int win = (wave * CT + tc) * 2 + (blk & 1);
           const int slot = (2 * win + (c8 >> 1)) ^ slot_swizzle(rho);
           rd_off[tc][cb] = rho * ROW_BYTES + slot * 16 + (c8 & 1) * 8;
         }
     }
-    // One k-step of matrix work: operands bf (both 32-column B tiles) and ixw are in registers, the
-    // A operands stream from record `sa` through two alternating registers; av[0] may already hold
-    // tile row 0 (`have0`).
-    floatx16 acc[VT][2];
-    half16 bf[2];
-    uint2 ixw;                                     // 4 x 16 index bits
+    // One k-step of matrix work: operands bf (the wave's 32-column B tiles) and ixw are in
+    // registers, the A operands stream from the records at `sa` through two alternating registers;
+    // av[0] may already hold tile row 0 (`have0`).  Tile row t = block row t / VT of the pair,
+    // 32-row tile t % VT of it.
+    floatx16 acc[RT][CT];
+    half16 bf[CT];
+    uint2 ixw[PAIR];                               // 4 x 16 index bits per block row
     half8 av[2];
-    auto read_a = [&](const char* sa, int tr) {
-      return *reinterpret_cast<const half8*>(sa + tr * kTileValBytes + lane * 16);
+    auto read_a = [&](const char* sa, int t) {
+      return *reinterpret_cast<const half8*>(sa + (t / VT) * REC + (t % VT) * kTileValBytes + lane * 16);
     };
     auto read_b_ix = [&](const char* sb, const char* sa) {
 #pragma unroll
-      for (int tc = 0; tc < 2; ++tc)
+      for (int tc = 0; tc < CT; ++tc)
 #pragma unroll
         for (int cb = 0; cb < 4; ++cb) {
           const short4v piece = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(short4v))(sb + rd_off[tc][cb]));
           const half4 ph = __builtin_bit_cast(half4, piece);
           bf[tc][4 * cb + 0] = ph[0]; bf[tc][4 * cb + 1] = ph[1]; bf[tc][4 * cb + 2] = ph[2]; bf[tc][4 * cb + 3] = ph[3];
         }
-      ixw = *reinterpret_cast<const uint2*>(sa + T_OFF + lane * 8);
+#pragma unroll
+      for (int pr = 0; pr < PAIR; ++pr) ixw[pr] = *reinterpret_cast<const uint2*>(sa + pr * REC + T_OFF + lane * 8);
     };
     auto multiply = [&](const char* sa, bool have0) {
       if (!have0) av[0] = read_a(sa, 0);
-      if (VT > 1) av[1] = read_a(sa, 1);
+      if (RT > 1) av[1] = read_a(sa, 1);
 #pragma unroll
-      for (int tr = 0; tr < VT; ++tr) {
-        const int ix = (int)((tr >> 1) ? ixw.y : ixw.x);
+      for (int t = 0; t < RT; ++t) {
+        const int tr = t % VT;
+        const int ix = (int)((tr >> 1) ? ixw[t / VT].y : ixw[t / VT].x);
 #pragma unroll
-        for (int tc = 0; tc < 2; ++tc) {
-          if (tr & 1) acc[tr][tc] = smfmac<1>(av[tr & 1], bf[tc], acc[tr][tc], ix);
-          else acc[tr][tc] = smfmac<0>(av[tr & 1], bf[tc], acc[tr][tc], ix);
+        for (int tc = 0; tc < CT; ++tc) {
+          if (tr & 1) acc[t][tc] = smfmac<1>(av[t & 1], bf[tc], acc[t][tc], ix);
+          else acc[t][tc] = smfmac<0>(av[t & 1], bf[tc], acc[t][tc], ix);
         }
-        if (tr + 2 < VT) av[tr & 1] = read_a(sa, tr + 2);
+        if (t + 2 < RT) av[t & 1] = read_a(sa, t + 2);
       }
     };
     // The two consumer waves that share a SIMD work half a k-step apart: the EARLY one reads its
@@ -454,9 +472,9 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
     barrier_only();                                // (the producers' start-up barrier)
     for (int t = 0; t < tw.count; ++t) {
 #pragma unroll
-      for (int tr = 0; tr < VT; ++tr)
+      for (int tr = 0; tr < RT; ++tr)
 #pragma unroll
-        for (int tc = 0; tc < 2; ++tc)
+        for (int tc = 0; tc < CT; ++tc)
 #pragma unroll
           for (int v = 0; v < 16; ++v) acc[tr][tc][v] = 0.f;
 
@@ -507,8 +525,8 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
 #ifdef VENOM_ABLATE
       if (kAbl & 8192) { br = 0; ct = 0; }         // experiment: every tile writes block (0, 0) of C
 #endif
-      const int64_t row0 = (int64_t)br * VT * 32;
-      const int64_t col0 = (int64_t)ct * BSC + wave * 64;
+      const int64_t row0 = (int64_t)br * RT * 32;   // (the block rows of a pair are neighbours: RT tiles in a row)
+      const int64_t col0 = (int64_t)ct * BSC + wave * WCOLS;
       // fused epilogue (the layer's bias, one per output row, then the activation), in fp32 on
       // the accumulators, one 32-row tile at a time right before it is stored: a ln holds rows
       // 8j + 4*(ln/32) + 0..3 of the tile
@@ -519,10 +537,9 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
           for (int j = 0; j < 4; ++j) {
             const half4 b4 = *reinterpret_cast<const half4*>(p.bias + row0 + tr * 32 + 8 * j + 4 * (ln >> 5));
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              acc[tr][0][4 * j + i] += (float)b4[i];
-              acc[tr][1][4 * j + i] += (float)b4[i];
-            }
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+              for (int tc = 0; tc < CT; ++tc) acc[tr][tc][4 * j + i] += (float)b4[i];
             __builtin_amdgcn_sched_barrier(0);
           }
         }
@@ -530,7 +547,7 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
         // temporaries would push accumulators out of registers, for the whole kernel)
         if (p.act == VENOM_ACT_GELU) {
 #pragma unroll
-          for (int tc = 0; tc < 2; ++tc)
+          for (int tc = 0; tc < CT; ++tc)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
               acc[tr][tc][v] = gelu_by_definition(acc[tr][tc][v]);
@@ -538,7 +555,7 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
             }
         } else if (p.act == VENOM_ACT_GELU_TANH) {
 #pragma unroll
-          for (int tc = 0; tc < 2; ++tc)
+          for (int tc = 0; tc < CT; ++tc)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
               acc[tr][tc][v] = gelu_tanh_form(acc[tr][tc][v]);
@@ -552,10 +569,10 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
         // 8-byte (fp16) or 16-byte (fp32) store straight from the accumulators; the two half-waves
         // write neighbouring runs, the tiles of a block row continue the same 2*V bytes of a token.
 #pragma unroll
-        for (int tr = 0; tr < VT; ++tr) {
+        for (int tr = 0; tr < RT; ++tr) {
           finish(tr);
 #pragma unroll
-          for (int tc = 0; tc < 2; ++tc) {
+          for (int tc = 0; tc < CT; ++tc) {
             const int64_t tok = col0 + tc * 32 + (ln & 31);
             if (tok < p.Ccols) {
 #pragma unroll
@@ -578,10 +595,10 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
       } else if constexpr (OUT_F32) {
         float* Cf = reinterpret_cast<float*>(p.C);
 #pragma unroll
-        for (int tr = 0; tr < VT; ++tr) {
+        for (int tr = 0; tr < RT; ++tr) {
           finish(tr);
 #pragma unroll
-          for (int tc = 0; tc < 2; ++tc) {
+          for (int tc = 0; tc < CT; ++tc) {
             const int64_t col = col0 + tc * 32 + (ln & 31);
             if (col < p.Ccols) {
 #pragma unroll
@@ -594,32 +611,35 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
           __builtin_amdgcn_sched_barrier(0);
         }
       } else {
-        // One 32 x 64 tile row at a time through this wave's 4 KB of the drained stage (the
-        // producers refill that stage only after the next barrier).  A staged row is 128 bytes;
-        // its 16-byte chunks are XOR-swizzled by bit 2 of the row so that the two half-waves,
-        // which write rows r and r+4, use different banks.
-        char* stg = const_cast<char*>(sb) + wave * 4096;
+        // One 32-row tile of the wave's columns at a time through this wave's share of the drained
+        // stage (the producers refill that stage only after the next barrier).  A staged row is
+        // 2*WCOLS bytes; its 16-byte chunks are XOR-swizzled by bit 2 of the row so that the two
+        // half-waves, which write rows r and r+4, use different banks.
+        constexpr int SROW = 2 * WCOLS;            // bytes of a staged row
+        constexpr int LPS = SROW / 16;             // lanes (16-byte chunks) per staged row
+        constexpr int SWZ = LPS / 2;               // chunk distance that changes the bank group
+        char* stg = const_cast<char*>(sb) + wave * (32 * SROW);
         _Float16* Ch = reinterpret_cast<_Float16*>(p.C);
-        const int chunk = ln & 7, rsub = ln >> 3;
+        const int chunk = ln % LPS, rsub = ln / LPS;
         const int64_t col = col0 + chunk * 8;
 #pragma unroll
-        for (int tr = 0; tr < VT; ++tr) {
+        for (int tr = 0; tr < RT; ++tr) {
           finish(tr);
 #pragma unroll
-          for (int tc = 0; tc < 2; ++tc) {
+          for (int tc = 0; tc < CT; ++tc) {
             const int c = tc * 32 + (ln & 31);
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
               const int r = 8 * (v >> 2) + 4 * (ln >> 5) + (v & 3);
-              const int sw = ((c >> 3) ^ (4 * ((r >> 2) & 1)));
-              *reinterpret_cast<_Float16*>(stg + r * 128 + sw * 16 + (c & 7) * 2) =
+              const int sw = ((c >> 3) ^ (SWZ * ((r >> 2) & 1)));
+              *reinterpret_cast<_Float16*>(stg + r * SROW + sw * 16 + (c & 7) * 2) =
                   (_Float16)acc[tr][tc][v];        // one rounding, nearest-even
             }
           }
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int r = i * 8 + rsub;
-            const uint4 val = *reinterpret_cast<const uint4*>(stg + r * 128 + ((chunk ^ (4 * ((r >> 2) & 1))) * 16));
+          for (int i = 0; i < 32 / (64 / LPS); ++i) {
+            const int r = i * (64 / LPS) + rsub;
+            const uint4 val = *reinterpret_cast<const uint4*>(stg + r * SROW + ((chunk ^ (SWZ * ((r >> 2) & 1))) * 16));
             if (col < p.Ccols) {
               typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
               u32x4* dst = reinterpret_cast<u32x4*>(Ch + (row0 + tr * 32 + r) * p.ldc + col);
@@ -647,36 +667,47 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
 struct Variant {
   const char* name;
   int V;       // block height it serves
+  int pair;    // block rows a workgroup owns (2: only where neighbouring block rows select the same columns)
   int bsc;     // columns per workgroup
   int threads;
   int lds;     // dynamic LDS bytes
   void (*fn[2][3])(SpmmParams);   // [fp32 output][mode]
 };
 
-template <int VT, int NC, int NA>
+template <int VT, int NC, int NA, int PAIR>
 constexpr int lds_bytes() {   // B ring, A ring, row-id ring (the output staging reuses a B stage)
-  return kStages * kStepRows * 128 * NC + NA * (VT * kTileValBytes + kTailBytes) + kRidSlots * kStepRows * 4;
+  return kStages * kStepRows * (128 / PAIR) * NC + NA * PAIR * (VT * kTileValBytes + kTailBytes) +
+         kRidSlots * kStepRows * 4;
 }
 
-#define VARIANT(NAME, VT, NC, NPB, NA)                                                         \
-  { NAME, (VT) * 32, 64 * (NC), 64 * ((NC) + (NPB) + 1), lds_bytes<VT, NC, NA>(),                \
-    { { spmm_kernel<VT, NC, NPB, NA, false, 0>, spmm_kernel<VT, NC, NPB, NA, false, 1>,                \
-        spmm_kernel<VT, NC, NPB, NA, false, 2> },                                                    \
-      { spmm_kernel<VT, NC, NPB, NA, true, 0>, spmm_kernel<VT, NC, NPB, NA, true, 1>,                  \
-        spmm_kernel<VT, NC, NPB, NA, true, 2> } } }
+#define VARIANT(NAME, VT, NC, NPB, NA, PAIR)                                                            \
+  { NAME, (VT) * 32, PAIR, (64 / (PAIR)) * (NC), 64 * ((NC) + (NPB) + 1), lds_bytes<VT, NC, NA, PAIR>(),       \
+    { { spmm_kernel<VT, NC, NPB, NA, false, 0, PAIR>, spmm_kernel<VT, NC, NPB, NA, false, 1, PAIR>,         \
+        spmm_kernel<VT, NC, NPB, NA, false, 2, PAIR> },                                                   \
+      { spmm_kernel<VT, NC, NPB, NA, true, 0, PAIR>, spmm_kernel<VT, NC, NPB, NA, true, 1, PAIR>,           \
+        spmm_kernel<VT, NC, NPB, NA, true, 2, PAIR> } } }
 
 static const Variant kVariants[] = {
-    VARIANT("v128_c512", 4, 8, 3, VENOM_NA512), VARIANT("v128_c256", 4, 4, 2, 9), VARIANT("v128_c128", 4, 2, 1, 10),
-    VARIANT("v96_c512", 3, 8, 3, 7),  VARIANT("v96_c256", 3, 4, 2, 10), VARIANT("v96_c128", 3, 2, 1, 10),
-    VARIANT("v64_c512", 2, 8, 3, 10), VARIANT("v64_c256", 2, 4, 2, 10), VARIANT("v64_c128", 2, 2, 1, 10),
-    VARIANT("v32_c512", 1, 8, 3, 10), VARIANT("v32_c256", 1, 4, 2, 10), VARIANT("v32_c128", 1, 2, 1, 10),
+    VARIANT("v128_c512", 4, 8, 3, VENOM_NA512, 1), VARIANT("v128_c256", 4, 4, 2, 9, 1), VARIANT("v128_c128", 4, 2, 1, 10, 1),
+    VARIANT("v96_c512", 3, 8, 3, 7, 1),  VARIANT("v96_c256", 3, 4, 2, 10, 1), VARIANT("v96_c128", 3, 2, 1, 10, 1),
+    VARIANT("v64_c512", 2, 8, 3, 10, 1), VARIANT("v64_c256", 2, 4, 2, 10, 1), VARIANT("v64_c128", 2, 2, 1, 10, 1),
+    VARIANT("v32_c512", 1, 8, 3, 10, 1), VARIANT("v32_c256", 1, 4, 2, 10, 1), VARIANT("v32_c128", 1, 2, 1, 10, 1),
+    // two block rows per workgroup (same selected columns in both: M = 4)
+    VARIANT("v128x2_c256", 4, 8, 2, 6, 2), VARIANT("v64x2_c256", 2, 8, 2, 6, 2),
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 int spmm_variant_count() { return kNumVariants; }
 const char* spmm_variant_name(int v) { return (v >= 0 && v < kNumVariants) ? kVariants[v].name : nullptr; }
 
-static int pick_variant(int V, int64_t Ccols, int64_t nbr) {
+static int pick_variant(int V, int M, int64_t Ccols, int64_t nbr) {
+  // M = 4 selects all four columns in every block, so neighbouring block rows gather the same rows
+  // of B: the paired tile halves the gather per matrix instruction (and doubles the passes over
+  // the A stream).  Measured at 8192 x 8192 x 2048: +7 % at V = 64, nothing at V = 128, where it is
+  // therefore only used on request.
+  if (M == kSelCols && V <= 64 && nbr % 2 == 0 && Ccols > 128)
+    for (int i = 0; i < kNumVariants; ++i)
+      if (kVariants[i].V == V && kVariants[i].pair == 2) return i;
   // The widest column tile that C fills at least half of: wide tiles re-read the A stream least
   // and measured fastest at every large shape tried; narrow C takes the narrow tiles.  When that
   // choice leaves more than half of the compute units without a tile (few block rows), the
@@ -684,7 +715,7 @@ static int pick_variant(int V, int64_t Ccols, int64_t nbr) {
   // 128-column tile (one gather wave, two consumers) never paid off.
   int best = -1;
   for (int i = 0; i < kNumVariants; ++i) {
-    if (kVariants[i].V != V) continue;
+    if (kVariants[i].V != V || kVariants[i].pair != 1) continue;
     if (best < 0) { best = i; continue; }
     const bool fits_i = 2 * Ccols > kVariants[i].bsc, fits_b = 2 * Ccols > kVariants[best].bsc;
     if (fits_i && (!fits_b || kVariants[i].bsc > kVariants[best].bsc)) best = i;
@@ -694,7 +725,7 @@ static int pick_variant(int V, int64_t Ccols, int64_t nbr) {
     const int64_t tiles = nbr * ((Ccols + 511) / 512);
     if (tiles <= 128)
       for (int i = 0; i < kNumVariants; ++i)
-        if (kVariants[i].V == V && kVariants[i].bsc == 256) best = i;
+        if (kVariants[i].V == V && kVariants[i].pair == 1 && kVariants[i].bsc == 256) best = i;
   }
   return best;
 }
@@ -704,9 +735,11 @@ venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, in
   const Layout& L = h.lay;
   if (!L.packed) return VENOM_ERR_UNSUPPORTED;
   if (L.R == 0 || Ccols == 0) return VENOM_OK;
-  if (variant < 0) variant = pick_variant(h.V, Ccols, L.Rb);
+  if (variant < 0) variant = pick_variant(h.V, h.M, Ccols, L.Rb);
   if (variant < 0 || variant >= kNumVariants || kVariants[variant].V != h.V) return VENOM_ERR_UNSUPPORTED;
   const Variant& var = kVariants[variant];
+  // a paired tile is only correct where both block rows of a pair gather the same rows of B
+  if (var.pair == 2 && (h.M != kSelCols || L.Rb % 2 != 0)) return VENOM_ERR_UNSUPPORTED;
   SpmmParams p{};
   p.arec = h.ws + L.off_arec;
   p.rowidx = reinterpret_cast<const int32_t*>(h.ws + L.off_rowidx);
@@ -735,12 +768,13 @@ venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, in
   }
 #endif
   const int64_t nct = (Ccols + var.bsc - 1) / var.bsc;
-  const int64_t total = nct * L.Rb;
+  const int64_t nbr = L.Rb / var.pair;
+  const int64_t total = nct * nbr;
   if (total > (int64_t)1 << 30 || L.steps > (int64_t)1 << 24) return VENOM_ERR_UNSUPPORTED;
   // gather offsets are formed as row * ldb_bytes + column bytes in 32 bits with a 24-bit multiply
   if (h.K >= ((int64_t)1 << 24) || ldb * 2 >= ((int64_t)1 << 24) || h.K * ldb * 2 >= ((int64_t)1 << 32))
     return VENOM_ERR_UNSUPPORTED;
-  p.nbr = (int)L.Rb; p.nct = (int)nct;
+  p.nbr = (int)nbr; p.nct = (int)nct;
   p.per_xcd = (int)((total + kNumXcd - 1) / kNumXcd);
   // one resident workgroup per compute unit (two where the tile is small enough to share a unit);
   // each walks per_xcd / (grid / 8) tiles

@@ -22,7 +22,8 @@ def setup(R, K, T, V, M, seed):
 
 
 @pytest.mark.parametrize("R,K,T,V,M", [(256, 384, 264, 128, 8), (384, 1280, 520, 128, 32), (192, 896, 136, 64, 16),
-                                       (128, 720, 72, 32, 10), (192, 130 * 4, 8, 96, 4), (64, 1400, 40, 32, 100)])
+                                       (128, 720, 72, 32, 10), (192, 130 * 4, 8, 96, 4), (64, 1400, 40, 32, 100),
+                                       (256, 256, 136, 128, 4), (512, 72, 264, 64, 4)])
 @pytest.mark.parametrize("out_dtype", [torch.float16, torch.float32])
 @pytest.mark.parametrize("activation", ["none", "gelu"])
 def test_linear_matches_oracle(R, K, T, V, M, out_dtype, activation):

@@ -28,8 +28,14 @@ def check(C_dev, Cs, E):
     return info
 
 
-def variants_for(V):
-    return [i for i, n in enumerate(binding.venom_spmm_variants()) if n.startswith(f"v{V}_")]
+def variants_for(V, M=None, R=None):
+    """Tile variants that serve block height V; with M and R given also the paired ones (two block
+    rows per workgroup), which are legal at M = 4 with an even number of block rows."""
+    names = binding.venom_spmm_variants()
+    out = [i for i, n in enumerate(names) if n.startswith(f"v{V}_")]
+    if M == 4 and R is not None and (R // V) % 2 == 0:
+        out += [i for i, n in enumerate(names) if n.startswith(f"v{V}x2_")]
+    return out
 
 
 CASES = [
@@ -42,6 +48,9 @@ CASES = [
     (64, 1400, 40, 32, 100),          # 2:100, G = 14: ragged last k-step
     (128, 336, 96, 64, 7),            # 2:7, G = 48
     (256, 64, 128, 128, 4),           # plain 2:4, G = 16
+    (512, 200, 520, 128, 4),          # plain 2:4, paired block rows, G = 50 (ragged), 2 pairs x 3 column tiles
+    (256, 96, 264, 64, 4),            # plain 2:4 at V = 64, 2 pairs
+    (384, 64, 72, 128, 4),            # odd number of block rows: no pairing
     (192, 512, 136, 96, 8),           # V = 96 (three 32-row tiles), two block rows
 ]
 
@@ -54,7 +63,7 @@ def test_spmm_matches_oracle_all_variants(R, K, C, V, M, out_dtype):
     ov, oc, om = o.compress(A, mask, V, M)
     Cs, E = o.spmm_fp64(ov, oc, om, R, K, V, M, B)
     Bd = to_dev_f16(B)
-    for var in [-1] + variants_for(V):
+    for var in [-1] + variants_for(V, M, R):
         out = torch.full((R, C), float("nan"), dtype=out_dtype, device=DEV)
         binding.venom_spmm(h, Bd, out=out, variant=var)
         torch.cuda.synchronize()
@@ -68,7 +77,7 @@ def test_identity_B_reproduces_expanded_matrix_exactly():
     h = compress_dev(A, mask, V, M)
     eye = torch.eye(K, dtype=torch.float16, device=DEV)
     want = np.where(mask != 0, A, 0).astype(np.uint16)
-    for var in [-1] + variants_for(V):
+    for var in [-1] + variants_for(V, M, R):
         out = binding.venom_spmm(h, eye, variant=var)
         torch.cuda.synchronize()
         got = out.cpu().numpy().view(np.uint16)
@@ -127,7 +136,8 @@ def test_argument_errors():
 
 @pytest.mark.parametrize("activation", ["none", "gelu", "gelu_tanh"])
 @pytest.mark.parametrize("out_dtype", [torch.float16, torch.float32])
-@pytest.mark.parametrize("R,K,C,V,M", [(256, 384, 264, 128, 8), (192, 896, 136, 64, 16), (128, 720, 72, 32, 10)])
+@pytest.mark.parametrize("R,K,C,V,M", [(256, 384, 264, 128, 8), (192, 896, 136, 64, 16), (128, 720, 72, 32, 10),
+                                       (256, 128, 264, 128, 4)])
 def test_fused_bias_and_activation(R, K, C, V, M, out_dtype, activation):
     A, mask, B = inputs.gen_problem(R, K, C, V, M, 1.0, seed=900 + R + M)
     rng = np.random.default_rng(77 + R)
@@ -140,7 +150,7 @@ def test_fused_bias_and_activation(R, K, C, V, M, out_dtype, activation):
             continue                      # the plain product is covered above
         Ys, Ey = o.epilogue_fp64(Cs, E, bias.view(np.uint16) if with_bias else None, activation)
         bias_d = torch.from_numpy(bias).to(DEV) if with_bias else None
-        for v in variants_for(V):
+        for v in variants_for(V, M, R):
             out = binding.venom_spmm(h, to_dev_f16(B), out_dtype=out_dtype, variant=v, bias=bias_d,
                                      activation=activation)
             ok, info = o.accept(out.float().cpu().numpy().astype(np.float64), Ys, Ey)
@@ -251,3 +261,14 @@ def test_runs_on_the_stream_it_is_given():
     Cs, E = o.spmm_fp64(ov, oc, om, R, K, V, M, B)
     check(out, Cs, E)
     assert torch.equal(out, out2)
+
+
+def test_paired_tiles_are_refused_where_block_rows_gather_different_rows():
+    R, K, C, V, M = 256, 256, 264, 128, 8
+    A, mask, B = inputs.gen_problem(R, K, C, V, M, 1.0, seed=13)
+    h = compress_dev(A, mask, V, M)
+    paired = [i for i, n in enumerate(binding.venom_spmm_variants()) if n.startswith(f"v{V}x2_")]
+    assert paired
+    with pytest.raises(binding.VenomError) as e:
+        binding.venom_spmm(h, to_dev_f16(B), variant=paired[0])
+    assert e.value.status == binding.VENOM_ERR_UNSUPPORTED
