@@ -142,6 +142,18 @@ venom_status_t venom_linear_scratch_bytes(const venom_handle_t* h, int64_t token
 venom_status_t venom_linear(const venom_handle_t* h, const void* X_f16_dev, int64_t ldx, int64_t tokens,
                             const void* bias_f16_dev, int activation, void* Y_dev, int64_t ldy, int y_dtype,
                             void* scratch_dev, size_t scratch_bytes, void* stream);
+/* venom_linear for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the transposed activations go into an array
+ * the library itself holds on every GPU it runs on (venom_linear_static_max_bytes() = 64 MiB per
+ * GPU, for the life of the process) instead of caller-owned scratch.  Needs K * tokens * 2 bytes
+ * <= that size, else VENOM_ERR_WORKSPACE; every other argument, restriction and status as
+ * venom_linear.  Calls no allocating routine.  All calls on one GPU share the one array: calls
+ * that overlap in time on the same GPU (different streams or threads) race on it; the array is
+ * fully rewritten by each call before it is read, so nothing needs clearing between calls. */
+size_t venom_linear_static_max_bytes(void);
+venom_status_t venom_linear_static(const venom_handle_t* h, const void* X_f16_dev, int64_t ldx, int64_t tokens,
+                                   const void* bias_f16_dev, int activation, void* Y_dev, int64_t ldy, int y_dtype,
+                                   void* stream);
 int venom_spmm_variant_count(void);
 /* Name of a variant ("v128_c512", ...) or NULL. */
 const char* venom_spmm_variant_name(int variant);

@@ -24,7 +24,7 @@ STATUS_NAMES = {
 # every symbol include/venom.h declares
 EXPORTS = ("venom_workspace_bytes", "venom_prune", "venom_compress", "venom_import", "venom_export", "venom_decompress",
            "venom_spmm", "venom_spmm_variant", "venom_spmm_bias_act", "venom_linear_scratch_bytes", "venom_linear",
-           "venom_spmm_variant_count", "venom_spmm_variant_name",
+           "venom_linear_static_max_bytes", "venom_linear_static", "venom_spmm_variant_count", "venom_spmm_variant_name",
            "venom_get_info", "venom_destroy", "venom_status_string")
 
 
@@ -69,6 +69,10 @@ def lib() -> ctypes.CDLL:
     L.venom_linear_scratch_bytes.argtypes = [c_void_p, c_int64, POINTER(c_size_t)]
     L.venom_linear.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_void_p, c_int, c_void_p, c_int64, c_int, c_void_p,
                                c_size_t, c_void_p]
+    L.venom_linear_static_max_bytes.argtypes = []
+    L.venom_linear_static_max_bytes.restype = c_size_t
+    L.venom_linear_static.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_void_p, c_int, c_void_p, c_int64, c_int,
+                                      c_void_p]
     L.venom_spmm_variant_count.argtypes = []
     L.venom_spmm_variant_name.argtypes = [c_int]
     L.venom_spmm_variant_name.restype = c_char_p
@@ -79,7 +83,8 @@ def lib() -> ctypes.CDLL:
     L.venom_status_string.argtypes = [c_int]
     L.venom_status_string.restype = c_char_p
     for name in ("venom_workspace_bytes", "venom_prune", "venom_compress", "venom_import", "venom_export", "venom_decompress",
-                 "venom_spmm", "venom_spmm_variant", "venom_spmm_bias_act", "venom_spmm_variant_count", "venom_get_info"):
+                 "venom_spmm", "venom_spmm_variant", "venom_spmm_bias_act", "venom_linear_scratch_bytes", "venom_linear",
+                 "venom_linear_static", "venom_spmm_variant_count", "venom_get_info"):
         getattr(L, name).restype = c_int
     _lib = L
     return L
@@ -264,6 +269,26 @@ def venom_linear(h: Handle, X, bias=None, activation="none", out=None, out_dtype
                             1 if out.dtype == torch.float32 else 0, _ptr(scratch), scratch.numel(), _stream_ptr(stream))
     if st != VENOM_OK:
         raise VenomError(st, "venom_linear")
+    return out
+
+
+def venom_linear_static_max_bytes() -> int:
+    return lib().venom_linear_static_max_bytes()
+
+
+def venom_linear_static(h: Handle, X, out, bias=None, activation="none", stream=None):
+    """venom_linear with the library's own static scratch: the caller passes the input and the output,
+    nothing is allocated here or in the library."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.stride(1) == 1 and X.shape[1] == h.K
+    tokens = X.shape[0]
+    assert out.dtype in (torch.float16, torch.float32) and out.stride(1) == 1 and out.shape == (tokens, h.R)
+    ldx = X.stride(0) if tokens > 1 else max(h.K, X.stride(0))
+    ldy = out.stride(0) if tokens > 1 else max(h.R, out.stride(0))
+    st = lib().venom_linear_static(h.ptr, _ptr(X), ldx, tokens, _ptr(bias), ACTIVATIONS[activation], _ptr(out), ldy,
+                                   1 if out.dtype == torch.float32 else 0, _stream_ptr(stream))
+    if st != VENOM_OK:
+        raise VenomError(st, "venom_linear_static")
     return out
 
 

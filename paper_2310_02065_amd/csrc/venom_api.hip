@@ -1,12 +1,37 @@
 // The C ABI: argument validation, workspace carving, handle lifetime.  All device work is in
 // venom_format.hip / venom_spmm.hip; nothing here allocates device memory.
+#include <mutex>
 #include <new>
 
 #include "venom_internal.h"
 
 using venom::Layout;
 
+// Scratch of venom_linear_static: the transposed activations of one call, held inside the library
+// for callers that cannot allocate.  One copy per GPU, loaded with the code object and kept until
+// the process ends.  In host code this name only stands for the symbol: the memory is reached
+// through the per-device address that hipGetSymbolAddress returns.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+// Device address of `scratch` on the current device, looked up once per device (each GPU holds its
+// own copy at its own address); null if the lookup fails.
+void* static_scratch_of_current_device() {
+  constexpr int kMaxDev = 64;
+  static std::mutex mu;
+  static void* addr[kMaxDev] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) return nullptr;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!addr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    addr[dev] = p;
+  }
+  return addr[dev];
+}
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
@@ -206,6 +231,21 @@ venom_status_t venom_linear(const venom_handle_t* h, const void* X_f16_dev, int6
                                      static_cast<uint16_t*>(scratch_dev), ldbt, st) != hipSuccess)
     return VENOM_ERR_HIP;
   return venom::launch_spmm(*h, scratch_dev, ldbt, tokens, bias_f16_dev, activation, Y_dev, ldy, y_dtype, 1, -1, st);
+}
+
+size_t venom_linear_static_max_bytes(void) { return kStaticScratchBytes; }
+
+venom_status_t venom_linear_static(const venom_handle_t* h, const void* X_f16_dev, int64_t ldx, int64_t tokens,
+                                   const void* bias_f16_dev, int activation, void* Y_dev, int64_t ldy, int y_dtype,
+                                   void* stream) {
+  if (!h || tokens < 0) return VENOM_ERR_INVALID_ARG;
+  size_t need = 0;
+  venom_linear_scratch_bytes(h, tokens, &need);
+  if (need > kStaticScratchBytes) return VENOM_ERR_WORKSPACE;   // K * tokens * 2 bytes beyond the array
+  void* ptr = static_scratch_of_current_device();
+  if (!ptr) return VENOM_ERR_HIP;
+  return venom_linear(h, X_f16_dev, ldx, tokens, bias_f16_dev, activation, Y_dev, ldy, y_dtype, ptr,
+                      kStaticScratchBytes, stream);
 }
 
 venom_status_t venom_spmm_variant(const venom_handle_t* h, const void* B_f16_dev, int64_t ldb, int64_t C_cols,
