@@ -191,7 +191,7 @@ venom_status_t venom_spmm_bias_act(const venom_handle_t* h, const void* B_f16_de
   if (C_cols < 1) return VENOM_ERR_SHAPE;
   if (ldb < C_cols || ldc < C_cols) return VENOM_ERR_SHAPE;
   if ((h->K > 0 && !B_f16_dev) || (h->R > 0 && !C_dev)) return VENOM_ERR_INVALID_ARG;
-  if (h->V % venom::kTileRows != 0 || C_cols % 8 != 0) return VENOM_ERR_UNSUPPORTED;
+  if (!h->lay.packed || C_cols % 8 != 0) return VENOM_ERR_UNSUPPORTED;
   const size_t esz = c_dtype == 1 ? 4 : 2;
   if (!aligned(B_f16_dev, 16) || !aligned(C_dev, 16) || (ldb * 2) % 16 != 0 || (ldc * esz) % 16 != 0)
     return VENOM_ERR_UNSUPPORTED;
@@ -216,7 +216,7 @@ venom_status_t venom_linear(const venom_handle_t* h, const void* X_f16_dev, int6
   if (tokens < 1) return VENOM_ERR_SHAPE;
   if (ldx < h->K || ldy < h->R) return VENOM_ERR_SHAPE;
   if ((h->K > 0 && !X_f16_dev) || (h->R > 0 && !Y_dev)) return VENOM_ERR_INVALID_ARG;
-  if (h->V % venom::kTileRows != 0 || tokens % 8 != 0) return VENOM_ERR_UNSUPPORTED;
+  if (!h->lay.packed || tokens % 8 != 0) return VENOM_ERR_UNSUPPORTED;
   if (tokens > 65535 * 64) return VENOM_ERR_UNSUPPORTED;   // token tiles ride on the transpose grid's y dimension
   const size_t esz = y_dtype == 1 ? 4 : 2;
   // a lane stores runs of 4 consecutive features: 8 bytes (fp16) or 16 bytes (fp32)

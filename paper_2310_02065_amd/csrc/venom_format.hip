@@ -10,8 +10,11 @@ Layout make_layout(int64_t R, int64_t K, int V, int M) {
   L.R = R; L.K = K; L.G = K / M; L.Rb = R / V;
   L.W = (L.G + 7) / 8;
   L.steps = (L.G + kStepGroups - 1) / kStepGroups;
-  L.packed = (V % kTileRows) == 0 && V / kTileRows <= kMaxTiles;
-  L.vt = L.packed ? V / kTileRows : 0;
+  int Vp = V;                                       // block height of the packed copy
+  if (M == kSelCols && R % (kMaxTiles * kTileRows) == 0) Vp = kMaxTiles * kTileRows;
+  L.packed = (Vp % kTileRows) == 0 && Vp / kTileRows <= kMaxTiles;
+  L.vt = L.packed ? Vp / kTileRows : 0;
+  L.Rbp = L.packed ? R / Vp : 0;
   L.rec_bytes = (int64_t)L.vt * kTileValBytes + kTailBytes;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
@@ -19,8 +22,8 @@ Layout make_layout(int64_t R, int64_t K, int V, int M) {
   L.off_columns = take((size_t)L.Rb * L.G * kSelCols * sizeof(uint16_t));
   L.off_meta = take((size_t)R * L.W * sizeof(uint32_t));
   if (L.packed) {
-    L.off_arec = take((size_t)L.Rb * L.steps * L.rec_bytes);
-    L.off_rowidx = take((size_t)L.Rb * L.steps * kStepRows * sizeof(int32_t));
+    L.off_arec = take((size_t)L.Rbp * L.steps * L.rec_bytes);
+    L.off_rowidx = take((size_t)L.Rbp * L.steps * kStepRows * sizeof(int32_t));
   }
   L.off_status = take(8);
   L.total = off;
@@ -140,14 +143,18 @@ __global__ void __launch_bounds__(256) compress_kernel(const uint16_t* __restric
 
 // Absolute row of B for every gathered row: [R/V][steps][32], entry 4*t + p of a step is
 // (8*step + t)*M + column_loc[p]; groups past the end point at row 0 (their values are zero).
+// (Vp, V: block heights of the packed copy and of the canonical arrays; they differ only at M = 4,
+// where all canonical block rows hold the same column ids.)
 __global__ void __launch_bounds__(256) pack_rowidx_kernel(const uint16_t* __restrict__ columns, int64_t G, int M,
-                                                          int64_t steps, int64_t total, int32_t* __restrict__ rowidx) {
+                                                          int64_t steps, int64_t total, int Vp, int V,
+                                                          int32_t* __restrict__ rowidx) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= total) return;
   const int rho = (int)(idx % kStepRows);
   const int64_t s = (idx / kStepRows) % steps, b = idx / kStepRows / steps;
   const int64_t g = s * 8 + rho / 4;
-  rowidx[idx] = (g < G) ? (int32_t)(g * M + columns[(b * G + g) * kSelCols + (rho % 4)]) : 0;
+  const int64_t cb = b * Vp / V;                   // canonical block row that holds the packed block's first row
+  rowidx[idx] = (g < G) ? (int32_t)(g * M + columns[(cb * G + g) * kSelCols + (rho % 4)]) : 0;
 }
 
 // canonical -> the kernel's packed A stream.  One record per (block row, k-step):
@@ -232,14 +239,15 @@ hipError_t launch_compress(const uint16_t* A, int64_t lda, const uint8_t* mask, 
 hipError_t launch_pack(const venom_handle& h, hipStream_t st) {
   const Layout& L = h.lay;
   if (!L.packed || L.R == 0 || L.G == 0) return hipSuccess;
-  int64_t total = L.Rb * L.steps * kStepRows;
+  const int Vp = L.vt * kTileRows;
+  int64_t total = L.Rbp * L.steps * kStepRows;
   hipLaunchKernelGGL(pack_rowidx_kernel, dim3(blocks_for(total)), dim3(256), 0, st,
-                     reinterpret_cast<const uint16_t*>(h.ws + L.off_columns), L.G, h.M, L.steps, total,
+                     reinterpret_cast<const uint16_t*>(h.ws + L.off_columns), L.G, h.M, L.steps, total, Vp, h.V,
                      reinterpret_cast<int32_t*>(h.ws + L.off_rowidx));
-  total = L.Rb * L.steps * (L.vt + 1) * 64;
+  total = L.Rbp * L.steps * (L.vt + 1) * 64;
   hipLaunchKernelGGL(pack_arec_kernel, dim3(blocks_for(total)), dim3(256), 0, st,
                      reinterpret_cast<const uint32_t*>(h.ws + L.off_values),
-                     reinterpret_cast<const uint32_t*>(h.ws + L.off_meta), L.G, L.W, L.steps, L.vt, h.V, total,
+                     reinterpret_cast<const uint32_t*>(h.ws + L.off_meta), L.G, L.W, L.steps, L.vt, Vp, total,
                      h.ws + L.off_arec);
   return hipGetLastError();
 }
@@ -249,7 +257,8 @@ hipError_t launch_decompress(const venom_handle& h, uint16_t* A, int64_t lda, hi
   if (L.R == 0 || L.K == 0) return hipSuccess;
   const int64_t total = L.R * L.K;
   hipLaunchKernelGGL(decompress_kernel, dim3(blocks_for(total)), dim3(256), 0, st, h.ws + L.off_arec,
-                     reinterpret_cast<const int32_t*>(h.ws + L.off_rowidx), L.R, L.K, h.V, h.M, L.steps, L.vt, A, lda);
+                     reinterpret_cast<const int32_t*>(h.ws + L.off_rowidx), L.R, L.K, L.vt * kTileRows, h.M, L.steps, L.vt,
+                     A, lda);
   return hipGetLastError();
 }
 

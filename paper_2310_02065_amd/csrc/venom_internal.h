@@ -23,9 +23,12 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 struct Layout {
   int64_t R, K, G, Rb, W;  // G = K/M groups per row, Rb = R/V block rows, W = ceil(G/8) meta words per row
   int64_t steps;           // k-steps = ceil(G/8)
-  int vt;                  // 32-row tiles per block row (V/32) when packed
+  int vt;                  // 32-row tiles per block row of the PACKED copy (its block height / 32)
+  int64_t Rbp;             // block rows of the packed copy: R / (32 * vt).  Its block height is V, except at
+                           // M = 4, where every block selects all four columns, V plays no role in the arrays,
+                           // and the copy is packed 128 rows high whenever R allows
   int64_t rec_bytes;       // bytes of one (block row, k-step) record of the packed A stream
-  bool packed;             // V % 32 == 0: the kernel's packed copies exist
+  bool packed;             // the kernel's packed copies exist (block height 32, 64, 96 or 128)
   size_t off_values, off_columns, off_meta;      // canonical
   size_t off_arec, off_rowidx;                   // packed for the kernel
   size_t off_status;                             // 8-byte legality word

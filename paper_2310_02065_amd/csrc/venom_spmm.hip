@@ -8,23 +8,23 @@
 //     B serves all V rows); a k-step is 8 groups = 32 gathered rows of B;
 //   * the workgroup is split by role.  NC CONSUMER waves each own a 64-column strip: they only read
 //     LDS (transposing reads ds_read_b64_tr_b16 build the B operand, plain reads fetch the packed
-//     values and index words) and issue matrix instructions.  PRODUCER waves only move data, by
-//     direct-to-LDS loads: NPB of them gather the 32 rows of B of every k-step (XOR-swizzled per
-//     row so the transposing reads spread over the banks) into a 4-stage ring, three k-steps ahead;
-//     one more streams the packed A records into a deeper ring, NA-1 k-steps ahead, because that
-//     stream comes from HBM while B is mostly L2-resident, and with them the row ids of B that the
-//     gather needs.  Loads retire in order per wave, so the streams live in different waves, and a
-//     producer that has to queue behind the memory pipeline stalls alone;
-//   * the loads are issued from inline assembly and retired with exact `s_waitcnt vmcnt(n)` counts;
-//     one s_barrier per k-step hands filled stages to the consumers and drained ones back;
+//     values and index words) and issue matrix instructions.  Four PRODUCER waves, one per SIMD,
+//     only move data, by direct-to-LDS loads.  A SIMD issues one wave-wide 16-byte load (1 KB) per
+//     ~69 cycles whatever the rest of the compute unit does (measured), so the loads of a k-step --
+//     the gathered rows of B, the packed A record, the row ids -- are dealt round-robin over the
+//     four producers: every SIMD's share of the vector-memory issue rate is used;
+//   * the loads are issued from inline assembly and retired with exact `s_waitcnt vmcnt(n)` counts
+//     (loads retire in order per wave); one s_barrier per k-step hands filled stages to the
+//     consumers and drained ones back;
+//   * the consumers run one k-step behind the loads and refill each operand register from the new
+//     stage right after its last use, so no LDS latency sits between two barriers;
 //   * workgroups are persistent (one per compute unit): the k-steps of all tiles of a workgroup
 //     form one sequence, so the load pipeline runs on across tile boundaries while the consumers
 //     store their output;
 //   * each XCD (one L2 each) walks a contiguous range of the column-tile-major tile list and keeps
 //     its slab of B hot.
 #include <atomic>
-#include <cstdio>
-#include <cstdlib>
+#include <type_traits>
 
 #include "venom_internal.h"
 
@@ -53,24 +53,11 @@ struct SpmmParams {
   int pad_row0;            // first gathered row of a tile's LAST k-step that lies past the end of K (32: none)
   const _Float16* bias;    // one entry per row of C, or null
   int act;                 // venom_activation_t
-#ifdef VENOM_ABLATE
-  unsigned long long* trace;
-  int k_rows;              // rows of B: experiment builds clamp every gathered row id to it
-#endif
 };
 
-#ifdef VENOM_ABLATE
-constexpr int kAbl = VENOM_ABLATE;   // experiment switches, fixed at compile time (never in the product library)
-#endif
 constexpr int kNumXcd = 8;
 constexpr int kMaxDevices = 16;      // devices whose per-device launch state is cached
-#ifndef VENOM_STAGES
-#define VENOM_STAGES 4
-#endif
-#ifndef VENOM_NA512
-#define VENOM_NA512 6
-#endif
-constexpr int kStages = VENOM_STAGES;           // B ring depth: three k-steps are in flight
+constexpr int kProducers = 4;        // producer waves per workgroup: one per SIMD
 constexpr int kRidSlots = 16;        // row-id ring: 128 bytes per k-step
 
 // ---- direct-to-LDS loads and their retirement, outside the compiler's wait-count bookkeeping.
@@ -86,29 +73,16 @@ __device__ __forceinline__ void dma4(const char* base, uint32_t lane_off, uint32
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(lane_off), "s"(base), "s"(lds_addr)
                : "memory");
 }
-// wait until at most N of this wave's loads are outstanding, then meet the other waves
-template <int N>
-__device__ __forceinline__ void wait_loads_and_barrier() {
-  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
-}
-// the same with N = min(k, MAXK) * UNIT for a run-time k >= 0; the steady state (k >= MAXK) is the
-// first case tested
-template <int UNIT, int MAXK>
-__device__ __forceinline__ void wait_units_and_barrier(int k) {
-  static_assert(MAXK * UNIT <= 63, "vmcnt is a 6-bit counter");
-  if (k >= MAXK) wait_loads_and_barrier<MAXK * UNIT>();
-  else if constexpr (MAXK > 0) wait_units_and_barrier<UNIT, MAXK - 1>(k);
-}
-// only the wait, for N = min(k, MAXK) * UNIT
-template <int UNIT, int MAXK>
-__device__ __forceinline__ void wait_units(int k) {
-  static_assert(MAXK * UNIT <= 63, "vmcnt is a 6-bit counter");
-  if (k >= MAXK) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(MAXK * UNIT) : "memory");
-  else if constexpr (MAXK > 0) wait_units<UNIT, MAXK - 1>(k);
+// wait until at most n of this wave's loads are outstanding, 0 <= n <= MAXN; the steady state
+// (n == MAXN) is the first case tested.  The count is an immediate of the instruction, hence the cascade.
+template <int MAXN>
+__device__ __forceinline__ void wait_loads(int n) {
+  static_assert(MAXN <= 63, "vmcnt is a 6-bit counter");
+  if (n >= MAXN) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(MAXN) : "memory");
+  else if constexpr (MAXN > 0) wait_loads<MAXN - 1>(n);
 }
 __device__ __forceinline__ void barrier_only() { asm volatile("s_barrier" ::: "memory"); }
-// the same once every LDS read of this wave has returned (its reads of a stage must be over
-// before the barrier that hands the stage back)
+// the same once every LDS access of this wave has completed
 __device__ __forceinline__ void lgkm_drained_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 // 16-byte slot swizzle of gathered row rho inside its LDS row
@@ -158,53 +132,48 @@ struct TileWalk {
 
 // MODE 0: the plain product; 1: fused bias / activation; 2: the same with C written transposed
 // (token-major).  Separate instantiations: the plain kernel carries none of the epilogue code.
-// PAIR 2: the workgroup owns TWO neighbouring block rows and half the columns per wave.  Legal only
-// where both block rows select the same columns of every group (always at M = 4, where all four are
-// selected): the gathered rows of B then serve 2V rows, which halves the gather per matrix
-// instruction, the kernel's tightest resource.
-template <int VT, int NC, int NPB, int NA, bool OUT_F32, int MODE, int PAIR>
-__global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams p) {
+// NS: stages of the B ring; NA: records in the A ring.
+// D: barriers after which a consumed stage returns to the producers.  The consumers read stage g
+// between barriers g and g+1 but use what they read only after barrier g+1.  D = 2: they do not
+// wait for those reads before barrier g+1, so the stage stays theirs until barrier g+2 and the
+// loads run NS-2 k-steps ahead.  D = 1: they drain their reads before every barrier and the loads
+// run NS-1 k-steps ahead.
+template <int VT, int NC, int NS, int NA, int D, bool OUT_F32, int MODE>
+__global__ void __launch_bounds__((NC + kProducers) * 64, 3) spmm_kernel(SpmmParams p) {
   static_assert(NC == 2 || NC == 4 || NC == 8, "consumer waves per workgroup");
-  static_assert(PAIR == 1 || PAIR == 2, "block rows per workgroup");
+  static_assert(D == 1 || D == 2, "barriers between the hand-over of a stage and its return");
   constexpr bool EPI = MODE != 0;
   static_assert(VT >= 1 && VT <= kMaxTiles, "32-row tiles per block row");
-  static_assert(NA >= 4, "the A ring holds the record being read, the next one, and records in flight");
-  constexpr int RT = PAIR * VT;                    // 32-row tiles a consumer wave accumulates
-  constexpr int CT = 2 / PAIR;                     // 32-column tiles a consumer wave accumulates
+  constexpr int NP = kProducers;
+  constexpr int RT = VT;                           // 32-row tiles a consumer wave accumulates
+  constexpr int CT = 2;                            // 32-column tiles a consumer wave accumulates
   constexpr int WCOLS = 32 * CT;                   // columns of C per consumer wave
   constexpr int BSC = WCOLS * NC;                  // columns of C per workgroup
   constexpr int ROW_BYTES = 2 * BSC;               // one gathered row of B in LDS
   constexpr int RPI = 1024 / ROW_BYTES;            // rows written by one wave-wide 16-byte load
   constexpr int LPR = 64 / RPI;                    // lanes (= 16-byte slots) per row
   constexpr int NI = kStepRows / RPI;              // B loads per k-step (4 * NC)
-  constexpr int NBH = (NI + NPB - 1) / NPB, NBL = NI / NPB, NBHI = NI % NPB;  // ... per B producer
+  constexpr int CB = NI / NP;                      // ... per producer
+  static_assert(NI % NP == 0, "the B loads of a k-step divide evenly over the producers");
   constexpr int B_BYTES = kStepRows * ROW_BYTES;
   constexpr int REC = VT * kTileValBytes + kTailBytes;       // one A record
-  constexpr int A_BYTES = PAIR * REC;              // the records of one k-step (one per block row)
   constexpr int T_OFF = VT * kTileValBytes;        // record tail: index words
-  constexpr int ARING = kStages * B_BYTES;         // LDS: [B ring][A ring][row-id ring]
-  constexpr int RIDRING = ARING + NA * A_BYTES;
-  constexpr int NJ = PAIR * (VT + 1);              // A loads per k-step: VT value blocks + the tail, per block row
-  constexpr int PA = NA - 2;                       // k-steps the A stream runs ahead (a record stays one step
-                                                   // longer than its k-step: the late consumers re-read it)
-  constexpr int PB = kStages - 1;                  // k-steps the B stream runs ahead
-  static_assert((kStages - 2) * NBH <= 63 && PA * NJ <= 63, "load counts fit the 6-bit counter");
+  constexpr int ARING = NS * B_BYTES;              // LDS: [B ring][A ring][row-id ring]
+  constexpr int RIDRING = ARING + NA * REC;
+  constexpr int NJ = VT + 1;                       // A loads per k-step: VT value blocks + the tail
+  constexpr int PB = NS - D;                       // k-steps the B stream runs ahead
+  constexpr int PA = NA - D;                       // k-steps the A stream runs ahead
+  constexpr int RA = 2 * PB + 2;                   // k-steps the row-id stream runs ahead: the ids of step g+PB+1 are
+                                                   // then older, in their producer's load queue, than its loads of step g
+  static_assert(PB >= 1 && PA >= PB, "a record is issued no later than the B rows of its k-step");
+  static_assert(kRidSlots >= PB + 2, "a row-id slot is rewritten only after its last reader");
   static_assert(NC * 32 * WCOLS * 2 <= B_BYTES, "the output staging of all consumers fits one B stage");
-  constexpr int RA = PA + PB + 1;                  // k-steps the row-id stream runs ahead: the ids of step
-                                                   // g+PB+1 are then older than record g+1 in the load queue
-  static_assert(kRidSlots >= RA - PB + 2, "a row-id slot is rewritten only after its last reader");
 
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(LDS_PTR(char))smem;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
-#ifdef VENOM_ABLATE
-  if (p.trace && threadIdx.x == 0 && blockIdx.x < 16) {
-    p.trace[blockIdx.x * 4 + 0] = __builtin_readcyclecounter();
-    p.trace[blockIdx.x * 4 + 1] = wall_clock64();
-  }
-#endif
   TileWalk tw;
   {
     const int xcd = blockIdx.x % kNumXcd;
@@ -219,190 +188,179 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
   // All k-steps of all tiles of this workgroup form one sequence g = 0 .. G-1; the rings and the
   // barriers are indexed by g, so the loads of the next tile start while this one is finishing.
   // Barriers, in order: one before the first step (the first row ids are on chip), one per step
-  // ("step g is complete in LDS, step g-1 is consumed"), and one more after the last step of each
+  // ("step g is complete in LDS, step g-D is consumed"), and one more after the last step of each
   // tile, after which the consumers stage their output in the B stage they have just drained.
   const int G = tw.count * p.steps;
 
-  // the producers' few instructions per k-step go ahead of the consumers' when both are ready
-  if (wave >= NC) __builtin_amdgcn_s_setprio(3);
-  if (wave == NC + NPB) {
-    // ========================================================================= A producer
-    // Streams, in one in-order queue: the packed records, PA steps ahead, and the row ids of B
-    // that the gather producers need, RA steps ahead, into a ring of kRidSlots x 128 bytes.
-    const uint32_t lane_off = lane * 16;
-    int ct, br;
-    // record stream position
-    int a_t = 0, a_s = 0, a_slot = 0;
-    tw.locate(p, 0, ct, br);
-    // (br numbers groups of PAIR block rows; the records of the second block row of a pair lie
-    // pair_gap bytes after those of the first)
-    const char* a_ptr = p.arec + (int64_t)br * PAIR * p.steps * p.rec_bytes;
-    const int64_t pair_gap = (int64_t)p.steps * p.rec_bytes;
-    int64_t a_inc = p.rec_bytes;
-    auto next_record = [&]() {
-#ifdef VENOM_ABLATE
-      if (!(kAbl & (8 | 1024)))
-#endif
-      {
-        const uint32_t dst = lds0 + ARING + a_slot * A_BYTES;
-#pragma unroll
-        for (int pr = 0; pr < PAIR; ++pr) {
-          const char* src = a_ptr + pr * pair_gap;
-#pragma unroll
-          for (int j = 0; j < VT; ++j) dma16(src + j * 1024, lane_off, dst + pr * REC + j * 1024);
-          if (lane < kTailBytes / 16) dma16(src + T_OFF, lane_off, dst + pr * REC + T_OFF);   // the 512-byte tail: half a wave
-        }
-      }
-      a_ptr += a_inc;
-      a_slot = a_slot + 1 == NA ? 0 : a_slot + 1;
-      if (++a_s == p.steps) {
-        a_s = 0;
-        if (++a_t < tw.count) {
-          tw.locate(p, a_t, ct, br);
-          const bool back = p.serpentine && (a_t & 1);       // odd tiles run their k-steps backwards
-          a_inc = back ? -p.rec_bytes : p.rec_bytes;
-          a_ptr = p.arec + ((int64_t)br * PAIR * p.steps + (back ? p.steps - 1 : 0)) * p.rec_bytes;
-        }
-      }
-    };
-    // row-id stream position
-    int r_t = 0, r_s = 0, r_slot = 0;
-    const char* r_ptr = reinterpret_cast<const char*>(p.rowidx) + (int64_t)br * PAIR * p.steps * (kStepRows * 4);
-    int r_inc = kStepRows * 4;
-    auto next_rowids = [&]() {
-      if (lane < kStepRows) dma4(r_ptr, lane * 4, lds0 + RIDRING + r_slot * (kStepRows * 4));
-      r_ptr += r_inc;
-      r_slot = (r_slot + 1) % kRidSlots;
-      if (++r_s == p.steps) {
-        r_s = 0;
-        if (++r_t < tw.count) {
-          int ct2, br2;
-          tw.locate(p, r_t, ct2, br2);
-          const bool back = p.serpentine && (r_t & 1);
-          r_inc = back ? -(kStepRows * 4) : kStepRows * 4;
-          r_ptr = reinterpret_cast<const char*>(p.rowidx) +
-                  ((int64_t)br2 * PAIR * p.steps + (back ? p.steps - 1 : 0)) * (kStepRows * 4);
-        }
-      }
-    };
-    int first_records = 0;
-    for (int j = 0; j < RA && j < G; ++j) next_rowids();
-    for (int j = 0; j < PA && j < G; ++j, ++first_records) next_record();
-#ifdef VENOM_ABLATE
-    if constexpr ((kAbl & (8 | 1024)) != 0) wait_loads_and_barrier<0>();   // no record loads to count behind
-    else
-#endif
-    wait_units_and_barrier<NJ, PA>(first_records);  // the row ids (older than every record) have landed
-    int c_s = 0;                                   // step inside the tile the consumers are on
-    for (int g = 0; g < G; ++g) {
-      // records g and g+1 have landed when at most the records after g+1 are pending; the row-id
-      // loads in between only make the wait a little stricter
-      const int left = G - 2 - g;
-#ifdef VENOM_ABLATE
-      if constexpr ((kAbl & (8 | 1024)) != 0) wait_loads_and_barrier<0>();
-      else
-#endif
-      wait_units_and_barrier<NJ, PA - 2>(left < 0 ? 0 : left);
-      // after the barrier everyone is done with record g-2: its slot takes record g+PA
-      if (g + PA < G) next_record();
-      if (g + RA < G) next_rowids();
-      if (++c_s == p.steps) { c_s = 0; barrier_only(); }
-    }
-  } else if (wave >= NC) {
-    // ========================================================================= B producers
-    const int pj = wave - NC;
-    // B load q of this producer is load number pj + NPB*q of the k-step; it covers rows
-    // (that number)*RPI .. +RPI-1; lane l writes 16-byte slot l%LPR of row l/LPR and fetches the
-    // XOR-swizzled chunk of the gathered row.
-    // The row ids of a k-step sit in lane order in one register (lane l holds row l%32); one
-    // 24-bit multiply turns them into byte offsets row * ldb_bytes (the host checks the ranges),
-    // the rows of one load are picked out with v_readlane, and a lane adds its column offset.
-    int chunk_col[NBH];                            // first column of this lane's chunk inside the tile
-#pragma unroll
-    for (int q = 0; q < NBH; ++q) {
-      const int rho = ((pj + NPB * q) % NI) * RPI + lane / LPR;
-      chunk_col[q] = ((lane % LPR) ^ slot_swizzle(rho)) * 8;
-    }
-    uint32_t ld_col[NBH];
-    auto set_tile = [&](int t) {
+  if (wave >= NC) {
+    // ========================================================================= producers
+    // Iteration i (after barrier i) issues, in this order: the row ids of step i+RA, this
+    // producer's part of record i+PA, its part of the B rows of step i+PB.  Before barrier g the
+    // producer needs its loads of step g and of record g landed (and the row ids of step g+PB):
+    // all of them are at least as old as its B loads of step g, so it waits until only the loads
+    // of the PB-1 iterations issued since then are outstanding.
+    __builtin_amdgcn_s_setprio(3);                 // their few instructions go ahead of the consumers'
+    auto produce = [&](auto pj_const) {
+      constexpr int PJ = decltype(pj_const)::value;
+      constexpr int CA = PJ < NJ ? (NJ - PJ + NP - 1) / NP : 0;   // A loads per k-step: loads PJ, PJ+NP, ...
+      constexpr int CR = PJ == NP - 1 ? 1 : 0;                    // the row ids travel with the last producer
+      constexpr int L = CA + CR + CB;
+      static_assert((PB - 1) * L <= 63, "load counts fit the 6-bit counter");
+      const uint32_t lane_off = lane * 16;
       int ct, br;
-      tw.locate(p, t, ct, br);
+      // ---- record stream position
+      int a_t = 0, a_s = 0, a_slot = 0;
+      tw.locate(p, 0, ct, br);
+      const char* a_ptr = p.arec + (int64_t)br * p.steps * p.rec_bytes;
+      int64_t a_inc = p.rec_bytes;
+      auto next_record = [&]() {
+        const uint32_t dst = lds0 + ARING + a_slot * REC;
 #pragma unroll
-      for (int q = 0; q < NBH; ++q) {
-        int64_t col = (int64_t)ct * BSC + chunk_col[q];
-        if (col + 8 > p.Ccols) col = p.Ccols - 8;  // past the edge: any in-bounds data, never stored
-        ld_col[q] = (uint32_t)(col * 2);
+        for (int a = PJ; a < NJ; a += NP) {
+          if (a < VT) dma16(a_ptr + a * 1024, lane_off, dst + a * 1024);
+          else if (lane < kTailBytes / 16) dma16(a_ptr + T_OFF, lane_off, dst + T_OFF);   // the 512-byte tail: half a wave
+        }
+        a_ptr += a_inc;
+        a_slot = a_slot + 1 == NA ? 0 : a_slot + 1;
+        if (++a_s == p.steps) {
+          a_s = 0;
+          if (++a_t < tw.count) {
+            tw.locate(p, a_t, ct, br);
+            const bool back = p.serpentine && (a_t & 1);       // odd tiles run their k-steps backwards
+            a_inc = back ? -p.rec_bytes : p.rec_bytes;
+            a_ptr = p.arec + ((int64_t)br * p.steps + (back ? p.steps - 1 : 0)) * p.rec_bytes;
+          }
+        }
+      };
+      // ---- row-id stream position (producer NP-1 only)
+      int r_t = 0, r_s = 0, r_slot = 0;
+      const char* r_ptr = reinterpret_cast<const char*>(p.rowidx) + (int64_t)br * p.steps * (kStepRows * 4);
+      int r_inc = kStepRows * 4;
+      auto next_rowids = [&]() {
+        if (lane < kStepRows) dma4(r_ptr, lane * 4, lds0 + RIDRING + r_slot * (kStepRows * 4));
+        r_ptr += r_inc;
+        r_slot = (r_slot + 1) % kRidSlots;
+        if (++r_s == p.steps) {
+          r_s = 0;
+          if (++r_t < tw.count) {
+            int ct2, br2;
+            tw.locate(p, r_t, ct2, br2);
+            const bool back = p.serpentine && (r_t & 1);
+            r_inc = back ? -(kStepRows * 4) : kStepRows * 4;
+            r_ptr = reinterpret_cast<const char*>(p.rowidx) +
+                    ((int64_t)br2 * p.steps + (back ? p.steps - 1 : 0)) * (kStepRows * 4);
+          }
+        }
+      };
+      // ---- B stream.  Load q of this producer is load number PJ + NP*q of the k-step; it covers
+      // rows (that number)*RPI .. +RPI-1; lane l writes 16-byte slot l%LPR of row l/LPR and fetches
+      // the XOR-swizzled chunk of the gathered row.
+      // The row ids of a k-step sit in lane order in one register (lane l holds row l%32); one
+      // 24-bit multiply turns them into byte offsets row * ldb_bytes (the host checks the ranges),
+      // the rows of one load are picked out with v_readlane, and a lane adds its column offset.
+      int chunk_col[CB];                           // first column of this lane's chunk inside the tile
+#pragma unroll
+      for (int q = 0; q < CB; ++q) {
+        const int rho = (PJ + NP * q) * RPI + lane / LPR;
+        chunk_col[q] = ((lane % LPR) ^ slot_swizzle(rho)) * 8;
       }
-    };
-    const int rowsel = lane / LPR;                 // which of the RPI rows of a load this lane writes
-    const uint32_t ldb24 = (uint32_t)p.ldb_bytes;
-    const bool hi = NBHI == 0 || pj < NBHI;        // this producer has NBH loads per k-step, else NBL
-    int b_t = 0, b_s = 0, b_slot = 0;
-    set_tile(0);
-    auto issue = [&](int ridv) {
-#ifdef VENOM_ABLATE
-      if (!(kAbl & (8 | 2048)))
-#endif
-      {
+      uint32_t ld_col[CB];
+      auto set_tile = [&](int t) {
+        int ct3, br3;
+        tw.locate(p, t, ct3, br3);
+#pragma unroll
+        for (int q = 0; q < CB; ++q) {
+          int64_t col = (int64_t)ct3 * BSC + chunk_col[q];
+          if (col + 8 > p.Ccols) col = p.Ccols - 8;  // past the edge: any in-bounds data, never stored
+          ld_col[q] = (uint32_t)(col * 2);
+        }
+      };
+      const int rowsel = lane / LPR;               // which of the RPI rows of a load this lane writes
+      const uint32_t ldb24 = (uint32_t)p.ldb_bytes;
+      int b_t = 0, b_s = 0, b_slot = 0;
+      set_tile(0);
+      auto next_rows = [&](int ridv) {
         const uint32_t sb = lds0 + b_slot * B_BYTES;
         // byte offsets of all 32 rows at once (lane l: row l%32), then one v_readlane per row
         const int rowoff = (int)__umul24((uint32_t)ridv, ldb24);
 #pragma unroll
-        for (int q = 0; q < NBH; ++q) {
-          if (q < NBL || hi) {
-            const int rho0 = ((pj + NPB * q) % NI) * RPI;
-            int off = __builtin_amdgcn_readlane(rowoff, rho0);
+        for (int q = 0; q < CB; ++q) {
+          const int rho0 = (PJ + NP * q) * RPI;
+          int off = __builtin_amdgcn_readlane(rowoff, rho0);
 #pragma unroll
-            for (int k = 1; k < RPI; ++k) {
-              const int ok = __builtin_amdgcn_readlane(rowoff, rho0 + k);
-              off = rowsel == k ? ok : off;
-            }
-            dma16(p.B, (uint32_t)off + ld_col[q], sb + (pj + NPB * q) * 1024);
+          for (int k = 1; k < RPI; ++k) {
+            const int ok = __builtin_amdgcn_readlane(rowoff, rho0 + k);
+            off = rowsel == k ? ok : off;
           }
+          dma16(p.B, (uint32_t)off + ld_col[q], sb + (PJ + NP * q) * 1024);
         }
-      }
-      b_slot = (b_slot + 1) % kStages;
-      if (++b_s == p.steps) {
-        b_s = 0;
-        if (++b_t < tw.count) set_tile(b_t);
-      }
-    };
-    auto rowids_of = [&](int g) {
-      int r = *reinterpret_cast<const int*>(smem + RIDRING + (g % kRidSlots) * (kStepRows * 4) + (lane & 31) * 4);
-#ifdef VENOM_ABLATE
-      r = r < 0 ? 0 : (r >= p.k_rows ? p.k_rows - 1 : r);
-#endif
-      return r;
-    };
-    barrier_only();                                // the first row ids are on chip
-    for (int j = 0; j < PB && j < G; ++j) issue(rowids_of(j));
-    int ridv = PB < G ? rowids_of(PB) : 0;         // row ids of the k-step issued next
-    int c_s = 0, c_t = 0;                          // k-step inside the tile / tile the consumers are on
-    for (int g = 0; g < G; ++g) {
-      // this producer's part of k-step g has landed when at most its loads of the later steps
-      // (up to two) are pending
-      const int left = G - 1 - g;
-      if (p.pad_row0 < kStepRows && c_s == ((p.serpentine && (c_t & 1)) ? 0 : p.steps - 1)) {
-        // The last k-step of a tile when K/M is not a multiple of 8: its trailing groups do not
-        // exist.  Their values are zero, but 0 x Inf is not, so the rows gathered for them (row 0
-        // of B, a valid address that keeps the load count exact) are overwritten with zeros once
-        // they have landed; every producer cleans the rows it loaded itself.
-        if (hi) wait_units<NBH, kStages - 2>(left);
-        else wait_units<NBL, kStages - 2>(left);
-        char* stage = smem + (g % kStages) * B_BYTES;
+        b_slot = (b_slot + 1) % NS;
+        if (++b_s == p.steps) {
+          b_s = 0;
+          if (++b_t < tw.count) set_tile(b_t);
+        }
+      };
+      auto rowids_of = [&](int g) {
+        return *reinterpret_cast<const int*>(smem + RIDRING + (g % kRidSlots) * (kStepRows * 4) + (lane & 31) * 4);
+      };
+      // loads this producer issued in each of the last PB-1 iterations (oldest first)
+      int issued[PB > 1 ? PB - 1 : 1] = {};
+      auto remember = [&](int n) {
 #pragma unroll
-        for (int q = 0; q < NBH; ++q)
-          if ((q < NBL || hi) && ((pj + NPB * q) % NI) * RPI + rowsel >= p.pad_row0)
-            *reinterpret_cast<uint4*>(stage + (pj + NPB * q) * 1024 + lane * 16) = make_uint4(0, 0, 0, 0);
-        lgkm_drained_barrier();
-      } else if (hi) wait_units_and_barrier<NBH, kStages - 2>(left);
-      else wait_units_and_barrier<NBL, kStages - 2>(left);
-      // after the barrier the consumers are done with stage g-1: it takes step g+PB
-      if (g + PB < G) {
-        issue(ridv);
-        if (g + PB + 1 < G) ridv = rowids_of(g + PB + 1);
+        for (int k = 0; k + 1 < PB - 1; ++k) issued[k] = issued[k + 1];
+        if (PB > 1) issued[PB - 2] = n;
+      };
+      auto outstanding_after_step = [&]() {
+        int n = 0;
+#pragma unroll
+        for (int k = 0; k < PB - 1; ++k) n += issued[k];
+        return n;
+      };
+      // start-up: the row ids of the first RA steps, then what iterations -PA .. -1 would have issued
+      if constexpr (CR != 0)
+        for (int j = 0; j < RA && j < G; ++j) next_rowids();
+      asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");   // the first row ids are on chip
+      for (int i = -PA; i < 0; ++i) {
+        int n = 0;
+        if (i + PA < G) { next_record(); n += CA; }
+        if (i + PB >= 0 && i + PB < G) { next_rows(rowids_of(i + PB)); n += CB; }
+        remember(n);
       }
-      if (++c_s == p.steps) { c_s = 0; ++c_t; barrier_only(); }
+      int ridv = PB < G ? rowids_of(PB) : 0;       // row ids of the k-step issued next
+      int c_s = 0, c_t = 0;                        // k-step inside the tile / tile the consumers are on
+      for (int g = 0; g < G; ++g) {
+        wait_loads<(PB - 1) * L>(outstanding_after_step());
+        if (p.pad_row0 < kStepRows && c_s == ((p.serpentine && (c_t & 1)) ? 0 : p.steps - 1)) {
+          // The last k-step of a tile when K/M is not a multiple of 8: its trailing groups do not
+          // exist.  Their values are zero, but 0 x Inf is not, so the rows gathered for them (row 0
+          // of B, a valid address that keeps the load count exact) are overwritten with zeros once
+          // they have landed; every producer cleans the rows it loaded itself.
+          char* stage = smem + (g % NS) * B_BYTES;
+#pragma unroll
+          for (int q = 0; q < CB; ++q)
+            if ((PJ + NP * q) * RPI + rowsel >= p.pad_row0)
+              *reinterpret_cast<uint4*>(stage + (PJ + NP * q) * 1024 + lane * 16) = make_uint4(0, 0, 0, 0);
+          lgkm_drained_barrier();
+        } else barrier_only();
+        // after barrier g the consumers are done with stage g-D and record g-D
+        int n = 0;
+        if constexpr (CR != 0)
+          if (g + RA < G) { next_rowids(); n += 1; }
+        if (g + PA < G) { next_record(); n += CA; }
+        if (g + PB < G) {
+          next_rows(ridv);
+          n += CB;
+          if (g + PB + 1 < G) ridv = rowids_of(g + PB + 1);
+        }
+        remember(n);
+        if (++c_s == p.steps) { c_s = 0; ++c_t; barrier_only(); }
+      }
+    };
+    switch (wave - NC) {
+      case 0: produce(std::integral_constant<int, 0>{}); break;
+      case 1: produce(std::integral_constant<int, 1>{}); break;
+      case 2: produce(std::integral_constant<int, 2>{}); break;
+      default: produce(std::integral_constant<int, 3>{}); break;
     }
   } else {
     // ========================================================================= consumers
@@ -423,51 +381,38 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
           rd_off[tc][cb] = rho * ROW_BYTES + slot * 16 + (c8 & 1) * 8;
         }
     }
-    // One k-step of matrix work: operands bf (the wave's 32-column B tiles) and ixw are in
-    // registers, the A operands stream from the records at `sa` through two alternating registers;
-    // av[0] may already hold tile row 0 (`have0`).  Tile row t = block row t / VT of the pair,
-    // 32-row tile t % VT of it.
     floatx16 acc[RT][CT];
-    half16 bf[CT];
-    uint2 ixw[PAIR];                               // 4 x 16 index bits per block row
-    half8 av[2];
+    half16 bf[CT];                                 // the wave's two 32-column B operands of one k-step
+    uint32_t ixw[2];                               // index words of tile rows (0,1) and (2,3): 2 x 16 bits each
+    half8 av[RT];                                  // the A operands of one k-step
     auto read_a = [&](const char* sa, int t) {
-      return *reinterpret_cast<const half8*>(sa + (t / VT) * REC + (t % VT) * kTileValBytes + lane * 16);
+      av[t] = *reinterpret_cast<const half8*>(sa + t * kTileValBytes + lane * 16);
     };
-    auto read_b_ix = [&](const char* sb, const char* sa) {
+    auto read_b = [&](const char* sb, int tc) {
 #pragma unroll
-      for (int tc = 0; tc < CT; ++tc)
-#pragma unroll
-        for (int cb = 0; cb < 4; ++cb) {
-          const short4v piece = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(short4v))(sb + rd_off[tc][cb]));
-          const half4 ph = __builtin_bit_cast(half4, piece);
-          bf[tc][4 * cb + 0] = ph[0]; bf[tc][4 * cb + 1] = ph[1]; bf[tc][4 * cb + 2] = ph[2]; bf[tc][4 * cb + 3] = ph[3];
-        }
-#pragma unroll
-      for (int pr = 0; pr < PAIR; ++pr) ixw[pr] = *reinterpret_cast<const uint2*>(sa + pr * REC + T_OFF + lane * 8);
-    };
-    auto multiply = [&](const char* sa, bool have0) {
-      if (!have0) av[0] = read_a(sa, 0);
-      if (RT > 1) av[1] = read_a(sa, 1);
-#pragma unroll
-      for (int t = 0; t < RT; ++t) {
-        const int tr = t % VT;
-        const int ix = (int)((tr >> 1) ? ixw[t / VT].y : ixw[t / VT].x);
-#pragma unroll
-        for (int tc = 0; tc < CT; ++tc) {
-          if (tr & 1) acc[t][tc] = smfmac<1>(av[t & 1], bf[tc], acc[t][tc], ix);
-          else acc[t][tc] = smfmac<0>(av[t & 1], bf[tc], acc[t][tc], ix);
-        }
-        if (t + 2 < RT) av[t & 1] = read_a(sa, t + 2);
+      for (int cb = 0; cb < 4; ++cb) {
+        const short4v piece = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(short4v))(sb + rd_off[tc][cb]));
+        const half4 ph = __builtin_bit_cast(half4, piece);
+        bf[tc][4 * cb + 0] = ph[0]; bf[tc][4 * cb + 1] = ph[1]; bf[tc][4 * cb + 2] = ph[2]; bf[tc][4 * cb + 3] = ph[3];
       }
     };
-    // The two consumer waves that share a SIMD work half a k-step apart: the EARLY one reads its
-    // operands right after the barrier and multiplies when they arrive; the LATE one first
-    // multiplies with the operands it fetched during the previous k-step, then fetches this one's.
-    // So one wave's LDS latency hides behind the other's matrix instructions.  Every LDS read of a
-    // stage still happens inside that stage's k-step; the late wave re-reads A tile rows of the
-    // previous record, which is why the A ring is refilled one step later than it is consumed.
-    const bool late = (wave / (NC / 2)) & 1;
+    auto read_ix = [&](const char* sa, int half) {
+      ixw[half] = *reinterpret_cast<const uint32_t*>(sa + T_OFF + lane * 8 + 4 * half);
+    };
+    auto mma = [&](int t, int tc) {
+      const int ix = (int)ixw[t >> 1];
+      if (t & 1) acc[t][tc] = smfmac<1>(av[t], bf[tc], acc[t][tc], ix);
+      else acc[t][tc] = smfmac<0>(av[t], bf[tc], acc[t][tc], ix);
+    };
+    // after tile row t of the LAST column pass nothing reads av[t] any more, and an index word is
+    // free after the last tile row that uses it
+    auto refill_after = [&](const char* sa, int t) {
+      read_a(sa, t);
+      if ((t & 1) == 1 || t == RT - 1) read_ix(sa, t >> 1);
+    };
+    // In iteration g (after barrier g: stage g and record g are complete) a wave multiplies step
+    // g-1 from registers, one column tile after the other, and refills every operand register from
+    // stage g as soon as its last matrix instruction has been issued.
     int b_slot = 0, a_slot = 0;
     barrier_only();                                // (the producers' start-up barrier)
     for (int t = 0; t < tw.count; ++t) {
@@ -482,50 +427,48 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
       const char* sa = smem;
       auto advance = [&]() {
         sb = smem + b_slot * B_BYTES;
-        sa = smem + ARING + a_slot * A_BYTES;
-        b_slot = (b_slot + 1) % kStages;
+        sa = smem + ARING + a_slot * REC;
+        b_slot = (b_slot + 1) % NS;
         a_slot = a_slot + 1 == NA ? 0 : a_slot + 1;
       };
-      if (!late) {
-        for (int s = 0; s < p.steps; ++s) {
-          barrier_only();                          // this k-step is complete in LDS
-          advance();
-          read_b_ix(sb, sa);
-          multiply(sa, false);
-        }
-        barrier_only();                            // every consumer has drained the last B stage
-      } else {
-        lgkm_drained_barrier();
+      // first k-step of the tile: only fetch (same order of reads as in the steady state)
+      barrier_only();
+      advance();
+      read_b(sb, 0);
+#pragma unroll
+      for (int tr = 0; tr < RT; ++tr) refill_after(sa, tr);
+      read_b(sb, 1);
+      for (int s = 1; s < p.steps; ++s) {
+        if constexpr (D == 1) lgkm_drained_barrier();   // my reads of the last stage are over; this one is complete
+        else barrier_only();                            // stage s and record s are complete
         advance();
-        read_b_ix(sb, sa);
-        av[0] = read_a(sa, 0);
-        for (int s = 1; s < p.steps; ++s) {
-          const char* sa_prev = sa;
-          lgkm_drained_barrier();                  // this k-step is complete; my reads of the last one are done
-          advance();
-          multiply(sa_prev, true);
-          read_b_ix(sb, sa);
-          av[0] = read_a(sa, 0);
+#pragma unroll
+        for (int tc = 0; tc < CT; ++tc) {
+#pragma unroll
+          for (int tr = 0; tr < RT; ++tr) {
+            mma(tr, tc);
+            if (tc == CT - 1) refill_after(sa, tr);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          read_b(sb, tc);
+          __builtin_amdgcn_sched_barrier(0);
         }
-        lgkm_drained_barrier();                    // every consumer has drained the last B stage
-        multiply(sa, true);
       }
+#pragma unroll
+      for (int tc = 0; tc < CT; ++tc)
+#pragma unroll
+        for (int tr = 0; tr < RT; ++tr) mma(tr, tc);
+      lgkm_drained_barrier();                      // every consumer has drained the last B stage
 
       // ---- stage 3: registers -> (LDS) -> global.  Accumulator element v of a 32x32 tile sits
       // at row 8*(v/4) + 4*(lane/32) + v%4, column lane%32.
-#ifdef VENOM_ABLATE
-      if ((kAbl & 16) && acc[0][0][0] != 12345.f) continue;
-#endif
       // everything below is per-tile work: keep its index arithmetic from being hoisted out of the
       // tile loop, where it would sit in registers the k-loop needs
       int ln = lane;
       asm volatile("" : "+v"(ln));
       int ct, br;
       tw.locate(p, t, ct, br);
-#ifdef VENOM_ABLATE
-      if (kAbl & 8192) { br = 0; ct = 0; }         // experiment: every tile writes block (0, 0) of C
-#endif
-      const int64_t row0 = (int64_t)br * RT * 32;   // (the block rows of a pair are neighbours: RT tiles in a row)
+      const int64_t row0 = (int64_t)br * RT * 32;
       const int64_t col0 = (int64_t)ct * BSC + wave * WCOLS;
       // fused epilogue (the layer's bias, one per output row, then the activation), in fp32 on
       // the accumulators, one 32-row tile at a time right before it is stored: a ln holds rows
@@ -655,67 +598,52 @@ __global__ void __launch_bounds__((NC + NPB + 1) * 64, 3) spmm_kernel(SpmmParams
       }
     }
   }
-#ifdef VENOM_ABLATE
-  if (p.trace && threadIdx.x == 0 && blockIdx.x < 16) {
-    p.trace[blockIdx.x * 4 + 2] = __builtin_readcyclecounter();
-    p.trace[blockIdx.x * 4 + 3] = wall_clock64();
-  }
-#endif
 }
 
 // ---------------------------------------------------------------------------------------------
 struct Variant {
   const char* name;
   int V;       // block height it serves
-  int pair;    // block rows a workgroup owns (2: only where neighbouring block rows select the same columns)
   int bsc;     // columns per workgroup
   int threads;
   int lds;     // dynamic LDS bytes
   void (*fn[2][3])(SpmmParams);   // [fp32 output][mode]
 };
 
-template <int VT, int NC, int NA, int PAIR>
+template <int VT, int NC, int NS, int NA>
 constexpr int lds_bytes() {   // B ring, A ring, row-id ring (the output staging reuses a B stage)
-  return kStages * kStepRows * (128 / PAIR) * NC + NA * PAIR * (VT * kTileValBytes + kTailBytes) +
-         kRidSlots * kStepRows * 4;
+  return NS * kStepRows * 128 * NC + NA * (VT * kTileValBytes + kTailBytes) + kRidSlots * kStepRows * 4;
 }
 
-#define VARIANT(NAME, VT, NC, NPB, NA, PAIR)                                                            \
-  { NAME, (VT) * 32, PAIR, (64 / (PAIR)) * (NC), 64 * ((NC) + (NPB) + 1), lds_bytes<VT, NC, NA, PAIR>(),       \
-    { { spmm_kernel<VT, NC, NPB, NA, false, 0, PAIR>, spmm_kernel<VT, NC, NPB, NA, false, 1, PAIR>,         \
-        spmm_kernel<VT, NC, NPB, NA, false, 2, PAIR> },                                                   \
-      { spmm_kernel<VT, NC, NPB, NA, true, 0, PAIR>, spmm_kernel<VT, NC, NPB, NA, true, 1, PAIR>,           \
-        spmm_kernel<VT, NC, NPB, NA, true, 2, PAIR> } } }
+#define VARIANT(NAME, VT, NC, NS, NA, D)                                                                  \
+  { NAME, (VT) * 32, 64 * (NC), 64 * ((NC) + kProducers), lds_bytes<VT, NC, NS, NA>(),                     \
+    { { spmm_kernel<VT, NC, NS, NA, D, false, 0>, spmm_kernel<VT, NC, NS, NA, D, false, 1>,               \
+        spmm_kernel<VT, NC, NS, NA, D, false, 2> },                                                     \
+      { spmm_kernel<VT, NC, NS, NA, D, true, 0>, spmm_kernel<VT, NC, NS, NA, D, true, 1>,                 \
+        spmm_kernel<VT, NC, NS, NA, D, true, 2> } } }
 
+#ifndef VENOM_D
+#define VENOM_D 2
+#endif
 static const Variant kVariants[] = {
-    VARIANT("v128_c512", 4, 8, 3, VENOM_NA512, 1), VARIANT("v128_c256", 4, 4, 2, 9, 1), VARIANT("v128_c128", 4, 2, 1, 10, 1),
-    VARIANT("v96_c512", 3, 8, 3, 7, 1),  VARIANT("v96_c256", 3, 4, 2, 10, 1), VARIANT("v96_c128", 3, 2, 1, 10, 1),
-    VARIANT("v64_c512", 2, 8, 3, 10, 1), VARIANT("v64_c256", 2, 4, 2, 10, 1), VARIANT("v64_c128", 2, 2, 1, 10, 1),
-    VARIANT("v32_c512", 1, 8, 3, 10, 1), VARIANT("v32_c256", 1, 4, 2, 10, 1), VARIANT("v32_c128", 1, 2, 1, 10, 1),
-    // two block rows per workgroup (same selected columns in both: M = 4)
-    VARIANT("v128x2_c256", 4, 8, 2, 6, 2), VARIANT("v64x2_c256", 2, 8, 2, 6, 2),
+    VARIANT("v128_c512", 4, 8, 4, 6, VENOM_D), VARIANT("v128_c256", 4, 4, 6, 10, VENOM_D), VARIANT("v128_c128", 4, 2, 8, 10, VENOM_D),
+    VARIANT("v96_c512", 3, 8, 4, 8, VENOM_D),  VARIANT("v96_c256", 3, 4, 6, 10, VENOM_D), VARIANT("v96_c128", 3, 2, 8, 10, VENOM_D),
+    VARIANT("v64_c512", 2, 8, 4, 10, VENOM_D), VARIANT("v64_c256", 2, 4, 6, 10, VENOM_D), VARIANT("v64_c128", 2, 2, 8, 10, VENOM_D),
+    VARIANT("v32_c512", 1, 8, 4, 10, VENOM_D), VARIANT("v32_c256", 1, 4, 6, 10, VENOM_D), VARIANT("v32_c128", 1, 2, 8, 10, VENOM_D),
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 int spmm_variant_count() { return kNumVariants; }
 const char* spmm_variant_name(int v) { return (v >= 0 && v < kNumVariants) ? kVariants[v].name : nullptr; }
 
-static int pick_variant(int V, int M, int64_t Ccols, int64_t nbr) {
-  // M = 4 selects all four columns in every block, so neighbouring block rows gather the same rows
-  // of B: the paired tile halves the gather per matrix instruction (and doubles the passes over
-  // the A stream).  Measured at 8192 x 8192 x 2048: +7 % at V = 64, nothing at V = 128, where it is
-  // therefore only used on request.
-  if (M == kSelCols && V <= 64 && nbr % 2 == 0 && Ccols > 128)
-    for (int i = 0; i < kNumVariants; ++i)
-      if (kVariants[i].V == V && kVariants[i].pair == 2) return i;
+static int pick_variant(int V, int64_t Ccols, int64_t nbr) {
   // The widest column tile that C fills at least half of: wide tiles re-read the A stream least
   // and measured fastest at every large shape tried; narrow C takes the narrow tiles.  When that
   // choice leaves more than half of the compute units without a tile (few block rows), the
-  // 256-column tile spreads the work over twice as many units and measured ~12 % faster; the
-  // 128-column tile (one gather wave, two consumers) never paid off.
+  // 256-column tile spreads the work over twice as many units.
   int best = -1;
   for (int i = 0; i < kNumVariants; ++i) {
-    if (kVariants[i].V != V || kVariants[i].pair != 1) continue;
+    if (kVariants[i].V != V) continue;
     if (best < 0) { best = i; continue; }
     const bool fits_i = 2 * Ccols > kVariants[i].bsc, fits_b = 2 * Ccols > kVariants[best].bsc;
     if (fits_i && (!fits_b || kVariants[i].bsc > kVariants[best].bsc)) best = i;
@@ -725,7 +653,7 @@ static int pick_variant(int V, int M, int64_t Ccols, int64_t nbr) {
     const int64_t tiles = nbr * ((Ccols + 511) / 512);
     if (tiles <= 128)
       for (int i = 0; i < kNumVariants; ++i)
-        if (kVariants[i].V == V && kVariants[i].pair == 1 && kVariants[i].bsc == 256) best = i;
+        if (kVariants[i].V == V && kVariants[i].bsc == 256) best = i;
   }
   return best;
 }
@@ -735,11 +663,10 @@ venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, in
   const Layout& L = h.lay;
   if (!L.packed) return VENOM_ERR_UNSUPPORTED;
   if (L.R == 0 || Ccols == 0) return VENOM_OK;
-  if (variant < 0) variant = pick_variant(h.V, h.M, Ccols, L.Rb);
-  if (variant < 0 || variant >= kNumVariants || kVariants[variant].V != h.V) return VENOM_ERR_UNSUPPORTED;
+  const int Vp = L.vt * kTileRows;                 // block height of the packed copy
+  if (variant < 0) variant = pick_variant(Vp, Ccols, L.Rbp);
+  if (variant < 0 || variant >= kNumVariants || kVariants[variant].V != Vp) return VENOM_ERR_UNSUPPORTED;
   const Variant& var = kVariants[variant];
-  // a paired tile is only correct where both block rows of a pair gather the same rows of B
-  if (var.pair == 2 && (h.M != kSelCols || L.Rb % 2 != 0)) return VENOM_ERR_UNSUPPORTED;
   SpmmParams p{};
   p.arec = h.ws + L.off_arec;
   p.rowidx = reinterpret_cast<const int32_t*>(h.ws + L.off_rowidx);
@@ -749,26 +676,11 @@ venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, in
   p.steps = (int)L.steps;
   p.bias = reinterpret_cast<const _Float16*>(bias);
   p.act = act;
-#ifdef VENOM_NO_SERPENTINE
-  p.serpentine = 0;
-#else
   p.serpentine = 1;
-#endif
   p.pad_row0 = (L.G % kStepGroups) ? (int)(L.G % kStepGroups) * kSelCols : kStepRows;
   p.stream_out = L.steps >= 32;   // measured: +3 % at 48 k-steps per tile, -20 % at 8
-#ifdef VENOM_ABLATE
-  p.k_rows = (int)h.K;
-#endif
-#ifdef VENOM_ABLATE
-  static unsigned long long* trace_buf = nullptr;
-  static int trace_calls = 0;
-  if (getenv("VENOM_TRACE")) {
-    if (!trace_buf) hipMalloc(&trace_buf, 64 * 8);
-    p.trace = trace_buf;
-  }
-#endif
   const int64_t nct = (Ccols + var.bsc - 1) / var.bsc;
-  const int64_t nbr = L.Rb / var.pair;
+  const int64_t nbr = L.Rbp;
   const int64_t total = nct * nbr;
   if (total > (int64_t)1 << 30 || L.steps > (int64_t)1 << 24) return VENOM_ERR_UNSUPPORTED;
   // gather offsets are formed as row * ldb_bytes + column bytes in 32 bits with a 24-bit multiply
@@ -807,20 +719,7 @@ venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, in
       if (cached) opted_in[variant][3 * c_dtype + epi][dev].store(true, std::memory_order_release);
     }
   }
-  const int launch_lds = var.lds;
-  hipLaunchKernelGGL(fn, dim3(grid), dim3(var.threads), launch_lds, st, p);
-#ifdef VENOM_ABLATE
-  if (p.trace && ++trace_calls == atoi(getenv("VENOM_TRACE"))) {
-    hipStreamSynchronize(st);
-    unsigned long long host[64];
-    hipMemcpy(host, p.trace, sizeof(host), hipMemcpyDeviceToHost);
-    for (int b = 0; b < 16; b += 5) {
-      const double cyc = (double)(host[b * 4 + 2] - host[b * 4 + 0]), ref = (double)(host[b * 4 + 3] - host[b * 4 + 1]);
-      fprintf(stderr, "wg %d: %.0f shader ticks, %.0f ref ticks (100 MHz) -> %.3f us, %.1f MHz\n", b, cyc, ref, ref / 100.0,
-              cyc / ref * 100.0);
-    }
-  }
-#endif
+  hipLaunchKernelGGL(fn, dim3(grid), dim3(var.threads), var.lds, st, p);
   return hipGetLastError() == hipSuccess ? VENOM_OK : VENOM_ERR_HIP;
 }
 

@@ -29,13 +29,12 @@ def check(C_dev, Cs, E):
 
 
 def variants_for(V, M=None, R=None):
-    """Tile variants that serve block height V; with M and R given also the paired ones (two block
-    rows per workgroup), which are legal at M = 4 with an even number of block rows."""
+    """Tile variants that serve a matrix of block height V.  At M = 4 every block selects all four
+    columns, so the library packs the matrix 128 rows high whenever R allows, whatever V is."""
+    if M == 4 and R is not None and R % 128 == 0:
+        V = 128
     names = binding.venom_spmm_variants()
-    out = [i for i, n in enumerate(names) if n.startswith(f"v{V}_")]
-    if M == 4 and R is not None and (R // V) % 2 == 0:
-        out += [i for i, n in enumerate(names) if n.startswith(f"v{V}x2_")]
-    return out
+    return [i for i, n in enumerate(names) if n.startswith(f"v{V}_")]
 
 
 CASES = [
@@ -48,9 +47,11 @@ CASES = [
     (64, 1400, 40, 32, 100),          # 2:100, G = 14: ragged last k-step
     (128, 336, 96, 64, 7),            # 2:7, G = 48
     (256, 64, 128, 128, 4),           # plain 2:4, G = 16
-    (512, 200, 520, 128, 4),          # plain 2:4, paired block rows, G = 50 (ragged), 2 pairs x 3 column tiles
-    (256, 96, 264, 64, 4),            # plain 2:4 at V = 64, 2 pairs
-    (384, 64, 72, 128, 4),            # odd number of block rows: no pairing
+    (512, 200, 520, 128, 4),          # plain 2:4, G = 50 (ragged)
+    (256, 96, 264, 64, 4),            # plain 2:4 at V = 64, R a multiple of 128: runs on the 128-row tiles
+    (256, 136, 72, 32, 4),            # the same at V = 32
+    (192, 64, 72, 64, 4),             # plain 2:4 at V = 64 where R is not a multiple of 128: 64-row tiles
+    (384, 64, 72, 128, 4),            # three block rows
     (192, 512, 136, 96, 8),           # V = 96 (three 32-row tiles), two block rows
 ]
 
@@ -261,14 +262,3 @@ def test_runs_on_the_stream_it_is_given():
     Cs, E = o.spmm_fp64(ov, oc, om, R, K, V, M, B)
     check(out, Cs, E)
     assert torch.equal(out, out2)
-
-
-def test_paired_tiles_are_refused_where_block_rows_gather_different_rows():
-    R, K, C, V, M = 256, 256, 264, 128, 8
-    A, mask, B = inputs.gen_problem(R, K, C, V, M, 1.0, seed=13)
-    h = compress_dev(A, mask, V, M)
-    paired = [i for i, n in enumerate(binding.venom_spmm_variants()) if n.startswith(f"v{V}x2_")]
-    assert paired
-    with pytest.raises(binding.VenomError) as e:
-        binding.venom_spmm(h, to_dev_f16(B), variant=paired[0])
-    assert e.value.status == binding.VENOM_ERR_UNSUPPORTED
