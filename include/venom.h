@@ -42,8 +42,10 @@ typedef enum {
   VENOM_OK = 0,
   VENOM_ERR_INVALID_ARG = 1, /* NULL where a pointer is required, negative size, bad enum value      */
   VENOM_ERR_SHAPE = 2,       /* R % V, K % M, M < 4, V < 1, C_cols < 1, leading dimension too small  */
-  VENOM_ERR_UNSUPPORTED = 3, /* N != 2; misaligned pointer / leading dimension; shape the kernel does
-                                not cover (venom_spmm needs V in {32,64,96,128}, C_cols % 8 == 0)   */
+  VENOM_ERR_UNSUPPORTED = 3, /* N != 2; misaligned pointer / leading dimension; shape the kernels do
+                                not cover (venom_spmm needs V in {32,64,96,128} -- any V at M = 4 when
+                                R % 128 == 0 --, C_cols % 8 == 0, K > 0; every call needs R/V <= 65535,
+                                M <= 1024 and R * K <= 2^38)                                         */
   VENOM_ERR_MASK_COLS = 4,   /* illegal mask: a V x M block uses more than 4 columns                 */
   VENOM_ERR_MASK_ROW = 5,    /* illegal mask: a row keeps more than 2 entries in a group of M        */
   VENOM_ERR_WORKSPACE = 6,   /* workspace NULL, misaligned (256 B) or smaller than required          */
@@ -76,13 +78,17 @@ venom_status_t venom_compress(const void* A_f16_dev, int64_t lda, const uint8_t*
                               size_t workspace_bytes, void* stream, venom_handle_t** out,
                               venom_violation_t* viol);
 
-/* Build a handle from canonical arrays already on the device (layout above).  The arrays are
- * copied into the workspace; they are trusted to be well formed (indices in range). */
+/* Section 3, the three arrays of the format as the persistent form of a compressed matrix: build
+ * a handle from canonical arrays already on the device (layout above).  The arrays are copied into
+ * the workspace and CHECKED there: column ids strictly increasing and below M, idx0 < idx1 in every
+ * nibble, unused nibbles zero; anything else returns VENOM_ERR_INVALID_ARG, no handle, and nothing
+ * is ever gathered from such arrays (value bits are free).  Synchronises `stream` once. */
 venom_status_t venom_import(const uint16_t* values_dev, const uint16_t* columns_dev, const uint32_t* meta_dev,
                             int64_t R, int64_t K, int V, int N, int M, void* workspace_dev,
                             size_t workspace_bytes, void* stream, venom_handle_t** out);
 
-/* Copy the canonical arrays out (any of the three destinations may be NULL to skip it).
+/* Section 3: the canonical arrays (values R x K/M x 2, m-indices R x K/M x 2 two-bit, column-loc
+ * R/V x K/M x 4) copied out; any of the three destinations may be NULL to skip it.
  * Asynchronous on `stream`. */
 venom_status_t venom_export(const venom_handle_t* h, uint16_t* values_dev, uint16_t* columns_dev,
                             uint32_t* meta_dev, void* stream);
@@ -94,7 +100,7 @@ venom_status_t venom_export(const venom_handle_t* h, uint16_t* values_dev, uint1
  * venom_compress).  Optionally accumulates, per block row, the kept and the total L1 mass as exact
  * integers in units of 2^-24 (every fp16 is a multiple of it; Inf/NaN count as 2^40):
  * energy = sum(kept) / sum(total).  kept_mass_dev / total_mass_dev: R/V uint64 each, or NULL.
- * Needs R/V <= 65535.  Asynchronous on `stream`. */
+ * Asynchronous on `stream`. */
 venom_status_t venom_prune(const void* A_f16_dev, int64_t lda, int64_t R, int64_t K, int V, int N, int M,
                            uint8_t* mask_dev, int64_t ldm, uint64_t* kept_mass_dev, uint64_t* total_mass_dev,
                            void* stream);
@@ -115,7 +121,8 @@ venom_status_t venom_decompress(const venom_handle_t* h, void* A_f16_dev, int64_
 venom_status_t venom_spmm(const venom_handle_t* h, const void* B_f16_dev, int64_t ldb, int64_t C_cols,
                           void* C_dev, int64_t ldc, int c_dtype, void* stream);
 
-/* Same product with an explicit kernel variant (tile shape / pipeline depth), for tuning sweeps.
+/* Section 4, the template parameters of the kernel (thread-block tile with BS_r = V, pipeline
+ * depth): the same product with an explicit kernel variant, for tuning sweeps.
  * variant < 0 selects automatically as venom_spmm does; an unknown or unsuitable variant returns
  * VENOM_ERR_UNSUPPORTED.  venom_spmm_variant_count() variants exist, numbered from 0. */
 venom_status_t venom_spmm_variant(const venom_handle_t* h, const void* B_f16_dev, int64_t ldb, int64_t C_cols,
@@ -158,6 +165,20 @@ int venom_spmm_variant_count(void);
 /* Name of a variant ("v128_c512", ...) or NULL. */
 const char* venom_spmm_variant_name(int variant);
 
+/* Section 5, the energy metric: sum of the kept L1 mass over the sum of the total L1 mass, from
+ * the per-block-row masses venom_prune wrote (exact integers, summed exactly on the host, divided
+ * once).  `energy` is a HOST pointer; 1.0 when the total mass is zero.  Synchronises `stream`. */
+venom_status_t venom_energy(const uint64_t* kept_mass_dev, const uint64_t* total_mass_dev, int64_t block_rows,
+                            double* energy, void* stream);
+
+/* Measurement aid (section 7 reports throughput against the hardware's matrix-instruction peak):
+ * launches a register-only loop of the 2:4 matrix instruction, 2 workgroups x 8 waves per compute
+ * unit, every wave issuing iterations x 8 instructions of 32768 useful FLOP each on pseudo-random
+ * operands.  The caller times it: the rate it finds is the instruction peak at the clock the GPU
+ * holds under that load.  sink_dev: 4 bytes of device memory (practically never written). */
+venom_status_t venom_probe_smfmac_rate(int iterations, void* sink_dev, void* stream);
+
+/* The shape a handle was built for (section 3: R x K in V:N:M); any output may be NULL. */
 venom_status_t venom_get_info(const venom_handle_t* h, int64_t* R, int64_t* K, int* V, int* N, int* M);
 void venom_destroy(venom_handle_t* h);
 const char* venom_status_string(venom_status_t s);

@@ -24,7 +24,8 @@ STATUS_NAMES = {
 # every symbol include/venom.h declares
 EXPORTS = ("venom_workspace_bytes", "venom_prune", "venom_compress", "venom_import", "venom_export", "venom_decompress",
            "venom_spmm", "venom_spmm_variant", "venom_spmm_bias_act", "venom_linear_scratch_bytes", "venom_linear",
-           "venom_linear_static_max_bytes", "venom_linear_static", "venom_spmm_variant_count", "venom_spmm_variant_name",
+           "venom_linear_static_max_bytes", "venom_linear_static", "venom_energy", "venom_probe_smfmac_rate",
+           "venom_spmm_variant_count", "venom_spmm_variant_name",
            "venom_get_info", "venom_destroy", "venom_status_string")
 
 
@@ -73,6 +74,8 @@ def lib() -> ctypes.CDLL:
     L.venom_linear_static_max_bytes.restype = c_size_t
     L.venom_linear_static.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_void_p, c_int, c_void_p, c_int64, c_int,
                                       c_void_p]
+    L.venom_energy.argtypes = [c_void_p, c_void_p, c_int64, POINTER(ctypes.c_double), c_void_p]
+    L.venom_probe_smfmac_rate.argtypes = [c_int, c_void_p, c_void_p]
     L.venom_spmm_variant_count.argtypes = []
     L.venom_spmm_variant_name.argtypes = [c_int]
     L.venom_spmm_variant_name.restype = c_char_p
@@ -84,7 +87,7 @@ def lib() -> ctypes.CDLL:
     L.venom_status_string.restype = c_char_p
     for name in ("venom_workspace_bytes", "venom_prune", "venom_compress", "venom_import", "venom_export", "venom_decompress",
                  "venom_spmm", "venom_spmm_variant", "venom_spmm_bias_act", "venom_linear_scratch_bytes", "venom_linear",
-                 "venom_linear_static", "venom_spmm_variant_count", "venom_get_info"):
+                 "venom_linear_static", "venom_energy", "venom_probe_smfmac_rate", "venom_spmm_variant_count", "venom_get_info"):
         getattr(L, name).restype = c_int
     _lib = L
     return L
@@ -176,11 +179,20 @@ def venom_prune(A, V, N, M, stream=None):
     return mask, kept, total
 
 
-def energy(kept_mass, total_mass) -> float:
-    """The energy metric from the per-block-row masses venom_prune returns (summed as Python integers)."""
-    k = sum(int(x) for x in kept_mass.cpu().tolist())
-    t = sum(int(x) for x in total_mass.cpu().tolist())
-    return k / t if t else 1.0
+def venom_energy(kept_mass, total_mass, stream=None) -> float:
+    """The energy metric from the per-block-row masses venom_prune returns."""
+    e = ctypes.c_double(0.0)
+    st = lib().venom_energy(_ptr(kept_mass), _ptr(total_mass), kept_mass.numel(), byref(e), _stream_ptr(stream))
+    if st != VENOM_OK:
+        raise VenomError(st, "venom_energy")
+    return e.value
+
+
+def venom_probe_smfmac_rate(iterations, sink, stream=None):
+    """Launches the register-only matrix-instruction loop (the caller times it)."""
+    st = lib().venom_probe_smfmac_rate(iterations, _ptr(sink), _stream_ptr(stream))
+    if st != VENOM_OK:
+        raise VenomError(st, "venom_probe_smfmac_rate")
 
 
 def venom_import(values, columns, meta, R, K, V, N, M, stream=None) -> Handle:

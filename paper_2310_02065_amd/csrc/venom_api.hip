@@ -42,6 +42,9 @@ venom_status_t check_shape(int64_t R, int64_t K, int V, int N, int M) {
   if (R % V != 0 || K % M != 0) return VENOM_ERR_SHAPE;
   if (M > 1024 || V >= (1 << 23)) return VENOM_ERR_UNSUPPORTED;
   if (K >= ((int64_t)1 << 31)) return VENOM_ERR_UNSUPPORTED;  // gathered row ids are 32-bit
+  // block rows ride on the y dimension of the compression grid; the element-wise format kernels
+  // number their threads with 32-bit block ids
+  if (R / V > 65535 || R > ((int64_t)1 << 38) / (K > 0 ? K : 1)) return VENOM_ERR_UNSUPPORTED;
   return VENOM_OK;
 }
 
@@ -79,7 +82,6 @@ venom_status_t venom_prune(const void* A_f16_dev, int64_t lda, int64_t R, int64_
   if ((R > 0 && K > 0) && (!A_f16_dev || !mask_dev)) return VENOM_ERR_INVALID_ARG;
   if (lda < K || ldm < K) return VENOM_ERR_SHAPE;
   if (!aligned(A_f16_dev, 2) || !aligned(kept_mass_dev, 8) || !aligned(total_mass_dev, 8)) return VENOM_ERR_UNSUPPORTED;
-  if (R / V > 65535) return VENOM_ERR_UNSUPPORTED;   // block rows ride on the grid's y dimension
   static_assert(sizeof(unsigned long long) == sizeof(uint64_t), "64-bit masses");
   const hipError_t e = venom::launch_prune(static_cast<const uint16_t*>(A_f16_dev), lda, R, K, V, M, mask_dev, ldm,
                                            reinterpret_cast<unsigned long long*>(kept_mass_dev),
@@ -147,6 +149,12 @@ venom_status_t venom_import(const uint16_t* values_dev, const uint16_t* columns_
       e = hipMemcpyAsync(h->ws + L.off_columns, columns_dev, (size_t)L.Rb * L.G * 8, hipMemcpyDeviceToDevice, st);
     if (e == hipSuccess)
       e = hipMemcpyAsync(h->ws + L.off_meta, meta_dev, (size_t)R * L.W * 4, hipMemcpyDeviceToDevice, st);
+    // the arrays come from outside: nothing is packed (or later gathered) from malformed ones
+    unsigned long long word = 0;
+    if (e == hipSuccess) e = venom::launch_validate(*h, st);
+    if (e == hipSuccess) e = hipMemcpyAsync(&word, h->ws + L.off_status, sizeof(word), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e == hipSuccess && word != ~0ull) { delete h; return VENOM_ERR_INVALID_ARG; }
     if (e == hipSuccess) e = venom::launch_pack(*h, st);
   }
   if (e != hipSuccess) { delete h; return VENOM_ERR_HIP; }
@@ -256,6 +264,34 @@ venom_status_t venom_spmm_variant(const venom_handle_t* h, const void* B_f16_dev
 venom_status_t venom_spmm(const venom_handle_t* h, const void* B_f16_dev, int64_t ldb, int64_t C_cols, void* C_dev,
                           int64_t ldc, int c_dtype, void* stream) {
   return venom_spmm_variant(h, B_f16_dev, ldb, C_cols, C_dev, ldc, c_dtype, -1, stream);
+}
+
+venom_status_t venom_energy(const uint64_t* kept_mass_dev, const uint64_t* total_mass_dev, int64_t block_rows,
+                            double* energy, void* stream) {
+  if (!energy || block_rows < 0 || (block_rows > 0 && (!kept_mass_dev || !total_mass_dev))) return VENOM_ERR_INVALID_ARG;
+  *energy = 1.0;
+  if (block_rows == 0) return VENOM_OK;
+  uint64_t* host = new (std::nothrow) uint64_t[2 * (size_t)block_rows];
+  if (!host) return VENOM_ERR_INVALID_ARG;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipError_t e = hipMemcpyAsync(host, kept_mass_dev, (size_t)block_rows * 8, hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess)
+    e = hipMemcpyAsync(host + block_rows, total_mass_dev, (size_t)block_rows * 8, hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  if (e == hipSuccess) {
+    // the masses are exact integers: sum them exactly (128 bits), divide once
+    unsigned __int128 kept = 0, total = 0;
+    for (int64_t b = 0; b < block_rows; ++b) { kept += host[b]; total += host[block_rows + b]; }
+    if (total != 0) *energy = (double)((long double)kept / (long double)total);
+  }
+  delete[] host;
+  return e == hipSuccess ? VENOM_OK : VENOM_ERR_HIP;
+}
+
+venom_status_t venom_probe_smfmac_rate(int iterations, void* sink_dev, void* stream) {
+  if (iterations < 1 || !sink_dev) return VENOM_ERR_INVALID_ARG;
+  return venom::launch_smfmac_probe(iterations, static_cast<float*>(sink_dev), static_cast<hipStream_t>(stream)) == hipSuccess
+             ? VENOM_OK : VENOM_ERR_HIP;
 }
 
 int venom_spmm_variant_count(void) { return venom::spmm_variant_count(); }

@@ -214,7 +214,40 @@ __global__ void __launch_bounds__(256) decompress_kernel(const char* __restrict_
   A[r * lda + k] = out;
 }
 
+// Imported canonical arrays are data from outside: one thread per (row, group) checks what the
+// gather and the matrix instruction rely on -- column ids strictly increasing and below M (rows of
+// the block's first row only), the two m-indices of a nibble ordered idx0 < idx1, unused nibbles of
+// the last metadata word zero.  Any offence sets the flag; nothing is gathered from such arrays.
+__global__ void __launch_bounds__(256) validate_kernel(const uint16_t* __restrict__ columns,
+                                                       const uint32_t* __restrict__ meta, int64_t R, int64_t G,
+                                                       int64_t W, int V, int M, unsigned long long* status) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= R * W * 8) return;
+  const int64_t r = idx / (W * 8), g = idx % (W * 8);
+  const uint32_t nib = (meta[r * W + g / 8] >> (4 * (g % 8))) & 0xfu;
+  bool bad = false;
+  if (g < G) {
+    bad = (nib & 3u) >= (nib >> 2);
+    if (r % V == 0) {
+      const uint16_t* c = columns + ((r / V) * G + g) * kSelCols;
+      bad = bad || !(c[0] < c[1] && c[1] < c[2] && c[2] < c[3] && c[3] < M);
+    }
+  } else bad = nib != 0;
+  if (bad) *status = 0;
+}
+
 static inline unsigned blocks_for(int64_t total) { return (unsigned)((total + 255) / 256); }
+
+hipError_t launch_validate(const venom_handle& h, hipStream_t st) {
+  const Layout& L = h.lay;
+  auto* status = reinterpret_cast<unsigned long long*>(h.ws + L.off_status);
+  hipLaunchKernelGGL(init_status_kernel, dim3(1), dim3(1), 0, st, status);
+  if (L.R > 0 && L.G > 0)
+    hipLaunchKernelGGL(validate_kernel, dim3(blocks_for(L.R * L.W * 8)), dim3(256), 0, st,
+                       reinterpret_cast<const uint16_t*>(h.ws + L.off_columns),
+                       reinterpret_cast<const uint32_t*>(h.ws + L.off_meta), L.R, L.G, L.W, h.V, h.M, status);
+  return hipGetLastError();
+}
 
 hipError_t launch_compress(const uint16_t* A, int64_t lda, const uint8_t* mask, int64_t ldm, const venom_handle& h,
                            hipStream_t st) {

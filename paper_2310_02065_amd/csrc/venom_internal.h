@@ -52,6 +52,8 @@ namespace venom {
 hipError_t launch_compress(const uint16_t* A, int64_t lda, const uint8_t* mask, int64_t ldm, const venom_handle& h,
                            hipStream_t st);
 hipError_t launch_pack(const venom_handle& h, hipStream_t st);
+// checks the canonical arrays in the workspace; the legality word reads ~0 afterwards iff they are well formed
+hipError_t launch_validate(const venom_handle& h, hipStream_t st);
 hipError_t launch_decompress(const venom_handle& h, uint16_t* A, int64_t lda, hipStream_t st);
 
 // ---- pruning (venom_prune.hip)
@@ -65,6 +67,9 @@ const char* spmm_variant_name(int v);
 // tokens_major != 0: C is written transposed (C[column][row], leading dimension ldc counts rows of A)
 venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, int64_t Ccols, const void* bias, int act,
                            void* C, int64_t ldc, int c_dtype, int tokens_major, int variant, hipStream_t st);
+// register-only loop of 2:4 matrix instructions, for the measured instruction peak (grid = one workgroup of 8 waves per
+// compute unit x 2)
+hipError_t launch_smfmac_probe(int iters, float* sink, hipStream_t st);
 hipError_t launch_transpose_tokens(const uint16_t* X, int64_t ldx, int64_t tokens, int64_t K, uint16_t* BT, int64_t ldbt,
                                    hipStream_t st);
 

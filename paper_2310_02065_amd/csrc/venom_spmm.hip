@@ -663,6 +663,7 @@ venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, in
   const Layout& L = h.lay;
   if (!L.packed) return VENOM_ERR_UNSUPPORTED;
   if (L.R == 0 || Ccols == 0) return VENOM_OK;
+  if (L.steps == 0) return VENOM_ERR_UNSUPPORTED;  // K = 0: there is no k-step to run the pipeline on
   const int Vp = L.vt * kTileRows;                 // block height of the packed copy
   if (variant < 0) variant = pick_variant(Vp, Ccols, L.Rbp);
   if (variant < 0 || variant >= kNumVariants || kVariants[variant].V != Vp) return VENOM_ERR_UNSUPPORTED;
@@ -721,6 +722,41 @@ venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, in
   }
   hipLaunchKernelGGL(fn, dim3(grid), dim3(var.threads), var.lds, st, p);
   return hipGetLastError() == hipSuccess ? VENOM_OK : VENOM_ERR_HIP;
+}
+
+// ---------------------------------------------------------------------------------------------
+// The 2:4 matrix instruction alone: every wave issues `iters` x 8 independent instructions on
+// register operands (pseudo-random fp16 values, so the multipliers toggle as they do on real data).
+// Timed by the caller, it gives the instruction peak this GPU sustains at the clock it holds under
+// that load: iters * 8 * 32768 useful FLOP per wave, 8 waves x 2 workgroups per compute unit.
+__global__ void __launch_bounds__(512) smfmac_probe_kernel(int iters, float* sink) {
+  const unsigned lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  unsigned x = (blockIdx.x * 8 + wave) * 64 + lane;
+  auto next_half = [&]() {
+    x = x * 1664525u + 1013904223u;
+    return (_Float16)((float)((x >> 9) & 0xfff) * (1.f / 2048.f) - 1.f);      // in [-1, 1)
+  };
+  half8 a; half16 b;
+  for (int e = 0; e < 8; ++e) a[e] = next_half();
+  for (int e = 0; e < 16; ++e) b[e] = next_half();
+  const int idx = 0x4e944e94 ^ (int)((lane & 1) * 0x00900090);                 // legal nibbles only
+  floatx16 acc[8] = {};
+  for (int i = 0; i < iters; ++i) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = smfmac<0>(a, b, acc[j], idx);
+  }
+  float s = 0.f;
+  for (int j = 0; j < 8; ++j) s += acc[j][0];
+  if (s == 12345.678f) sink[0] = s;              // keeps the loop alive; practically never true
+}
+
+hipError_t launch_smfmac_probe(int iters, float* sink, hipStream_t st) {
+  int dev = 0, cus = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(smfmac_probe_kernel, dim3(2 * cus), dim3(512), 0, st, iters, sink);
+  return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------------

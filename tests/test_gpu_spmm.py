@@ -262,3 +262,28 @@ def test_runs_on_the_stream_it_is_given():
     Cs, E = o.spmm_fp64(ov, oc, om, R, K, V, M, B)
     check(out, Cs, E)
     assert torch.equal(out, out2)
+
+
+def test_k_equal_zero_is_refused_not_run():
+    A = torch.zeros((128, 0), dtype=torch.float16, device=DEV)
+    mask = torch.zeros((128, 0), dtype=torch.uint8, device=DEV)
+    h = binding.venom_compress(A, mask, 128, 2, 8)
+    out = torch.full((128, 64), 3.0, dtype=torch.float16, device=DEV)
+    with pytest.raises(binding.VenomError) as e:
+        binding.venom_spmm(h, torch.zeros((0, 64), dtype=torch.float16, device=DEV), out=out)
+    assert e.value.status == binding.VENOM_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    assert bool((out == 3.0).all())
+
+
+def test_matrix_instruction_probe_runs():
+    sink = torch.zeros(1, dtype=torch.float32, device=DEV)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    binding.venom_probe_smfmac_rate(200, sink)
+    a.record()
+    binding.venom_probe_smfmac_rate(2000, sink)
+    b.record()
+    torch.cuda.synchronize()
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    tflops = 2000 * 8 * 32768 * 16 * cus / (a.elapsed_time(b) * 1e-3) / 1e12
+    assert 500 < tflops < 2600, tflops      # useful FLOP/s of the instruction alone: below the 2.5 PFLOP/s spec peak

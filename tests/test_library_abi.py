@@ -52,6 +52,9 @@ def test_workspace_sizing_and_shape_errors(L):
     assert L.venom_workspace_bytes(256, 256, 64, 1, 8, ctypes.byref(n)) == binding.VENOM_ERR_UNSUPPORTED
     assert L.venom_workspace_bytes(-1, 256, 64, 2, 8, ctypes.byref(n)) == binding.VENOM_ERR_INVALID_ARG
     assert L.venom_workspace_bytes(256, 256, 64, 2, 8, None) == binding.VENOM_ERR_INVALID_ARG
+    # more block rows than the compression grid carries: refused up front, as the header promises
+    assert L.venom_workspace_bytes(65536 * 2, 64, 2, 2, 8, ctypes.byref(n)) == binding.VENOM_ERR_UNSUPPORTED
+    assert L.venom_workspace_bytes(65535 * 2, 64, 2, 2, 8, ctypes.byref(n)) == binding.VENOM_OK
 
 
 def test_null_handle_and_variant_table(L):
