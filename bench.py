@@ -77,6 +77,8 @@ def main():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="skip the table of the other workloads")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--settle", type=int, default=400,
+                    help="untimed launches of the product kernel before the warm-up (profiling runs use fewer)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch three plain 1 GiB device copies (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -190,7 +192,7 @@ def main():
     # clock: the first launches after any change of load run 10-20 % slower, whatever ran before.
     # The figure of merit is the throughput of a long-running job, so the kernel runs untimed until
     # then (reported as settle_launches); the W warm-up steps and the K timed steps follow directly.
-    settle_launches = 400
+    settle_launches = max(0, args.settle)
     for _ in range(settle_launches):
         step()
     ms_wall, ms_avg, ms_med, ms_min = timed(step, args.steps, args.warmup)

@@ -206,24 +206,29 @@ __global__ void __launch_bounds__((NC + kProducers) * 64, 3) spmm_kernel(SpmmPar
       constexpr int CR = PJ == NP - 1 ? 1 : 0;                    // the row ids travel with the last producer
       constexpr int L = CA + CR + CB;
       static_assert((PB - 1) * L <= 63, "load counts fit the 6-bit counter");
+      // A producer is never ahead of the barrier it is about to meet: every instruction of its loop
+      // body lengthens the k-step (a wave issues nothing else while the address unit takes one of
+      // its loads, ~70 cycles, and instructions between two loads are not hidden behind them:
+      // measured).  So the streams advance by plain increments, ring positions wrap by compare and
+      // select, and everything that depends on the tile is recomputed in a branch taken once per tile.
       const uint32_t lane_off = lane * 16;
       int ct, br;
-      // ---- record stream position
-      int a_t = 0, a_s = 0, a_slot = 0;
+      // ---- record stream: record pointer, LDS slot address, k-steps left in its tile
       tw.locate(p, 0, ct, br);
       const char* a_ptr = p.arec + (int64_t)br * p.steps * p.rec_bytes;
       int64_t a_inc = p.rec_bytes;
+      uint32_t a_lds = lds0 + ARING;
+      int a_left = p.steps, a_t = 0;
       auto next_record = [&]() {
-        const uint32_t dst = lds0 + ARING + a_slot * REC;
 #pragma unroll
         for (int a = PJ; a < NJ; a += NP) {
-          if (a < VT) dma16(a_ptr + a * 1024, lane_off, dst + a * 1024);
-          else if (lane < kTailBytes / 16) dma16(a_ptr + T_OFF, lane_off, dst + T_OFF);   // the 512-byte tail: half a wave
+          if (a < VT) dma16(a_ptr + a * 1024, lane_off, a_lds + a * 1024);
+          else if (lane < kTailBytes / 16) dma16(a_ptr + T_OFF, lane_off, a_lds + T_OFF);   // the 512-byte tail: half a wave
         }
         a_ptr += a_inc;
-        a_slot = a_slot + 1 == NA ? 0 : a_slot + 1;
-        if (++a_s == p.steps) {
-          a_s = 0;
+        a_lds = a_lds + REC == lds0 + ARING + NA * REC ? lds0 + ARING : a_lds + REC;
+        if (--a_left == 0) {
+          a_left = p.steps;
           if (++a_t < tw.count) {
             tw.locate(p, a_t, ct, br);
             const bool back = p.serpentine && (a_t & 1);       // odd tiles run their k-steps backwards
@@ -232,16 +237,17 @@ __global__ void __launch_bounds__((NC + kProducers) * 64, 3) spmm_kernel(SpmmPar
           }
         }
       };
-      // ---- row-id stream position (producer NP-1 only)
-      int r_t = 0, r_s = 0, r_slot = 0;
+      // ---- row-id stream (producer NP-1 only)
       const char* r_ptr = reinterpret_cast<const char*>(p.rowidx) + (int64_t)br * p.steps * (kStepRows * 4);
       int r_inc = kStepRows * 4;
+      uint32_t r_lds = lds0 + RIDRING;
+      int r_left = p.steps, r_t = 0;
       auto next_rowids = [&]() {
-        if (lane < kStepRows) dma4(r_ptr, lane * 4, lds0 + RIDRING + r_slot * (kStepRows * 4));
+        if (lane < kStepRows) dma4(r_ptr, lane * 4, r_lds);
         r_ptr += r_inc;
-        r_slot = (r_slot + 1) % kRidSlots;
-        if (++r_s == p.steps) {
-          r_s = 0;
+        r_lds = r_lds + kStepRows * 4 == lds0 + RIDRING + kRidSlots * kStepRows * 4 ? lds0 + RIDRING : r_lds + kStepRows * 4;
+        if (--r_left == 0) {
+          r_left = p.steps;
           if (++r_t < tw.count) {
             int ct2, br2;
             tw.locate(p, r_t, ct2, br2);
@@ -254,10 +260,9 @@ __global__ void __launch_bounds__((NC + kProducers) * 64, 3) spmm_kernel(SpmmPar
       };
       // ---- B stream.  Load q of this producer is load number PJ + NP*q of the k-step; it covers
       // rows (that number)*RPI .. +RPI-1; lane l writes 16-byte slot l%LPR of row l/LPR and fetches
-      // the XOR-swizzled chunk of the gathered row.
-      // The row ids of a k-step sit in lane order in one register (lane l holds row l%32); one
-      // 24-bit multiply turns them into byte offsets row * ldb_bytes (the host checks the ranges),
-      // the rows of one load are picked out with v_readlane, and a lane adds its column offset.
+      // the XOR-swizzled chunk of the gathered row.  A lane reads the id of its row from the row-id
+      // ring (one LDS read per load, all of them before the record loads so that their latency is
+      // covered) and forms the byte offset with one multiply-add (the host checks the 24-bit ranges).
       int chunk_col[CB];                           // first column of this lane's chunk inside the tile
 #pragma unroll
       for (int q = 0; q < CB; ++q) {
@@ -277,31 +282,29 @@ __global__ void __launch_bounds__((NC + kProducers) * 64, 3) spmm_kernel(SpmmPar
       };
       const int rowsel = lane / LPR;               // which of the RPI rows of a load this lane writes
       const uint32_t ldb24 = (uint32_t)p.ldb_bytes;
-      int b_t = 0, b_s = 0, b_slot = 0;
+      uint32_t b_lds = lds0 + PJ * 1024;           // this producer's first row in the stage it fills next
+      const char* rid_rd = smem + RIDRING + rowsel * 4;   // this lane's entry of the ring slot it reads next
+      int b_left = p.steps, b_t = 0;
       set_tile(0);
-      auto next_rows = [&](int ridv) {
-        const uint32_t sb = lds0 + b_slot * B_BYTES;
-        // byte offsets of all 32 rows at once (lane l: row l%32), then one v_readlane per row
-        const int rowoff = (int)__umul24((uint32_t)ridv, ldb24);
+      int rid[CB];
+      auto read_rowids = [&]() {
 #pragma unroll
-        for (int q = 0; q < CB; ++q) {
-          const int rho0 = (PJ + NP * q) * RPI;
-          int off = __builtin_amdgcn_readlane(rowoff, rho0);
+        for (int q = 0; q < CB; ++q) rid[q] = *reinterpret_cast<const int*>(rid_rd + (PJ + NP * q) * RPI * 4);
+        rid_rd = rid_rd + kStepRows * 4 == smem + RIDRING + rowsel * 4 + kRidSlots * kStepRows * 4
+                     ? smem + RIDRING + rowsel * 4 : rid_rd + kStepRows * 4;
+      };
+      auto next_rows = [&]() {
+        uint32_t off[CB];
 #pragma unroll
-          for (int k = 1; k < RPI; ++k) {
-            const int ok = __builtin_amdgcn_readlane(rowoff, rho0 + k);
-            off = rowsel == k ? ok : off;
-          }
-          dma16(p.B, (uint32_t)off + ld_col[q], sb + (PJ + NP * q) * 1024);
-        }
-        b_slot = (b_slot + 1) % NS;
-        if (++b_s == p.steps) {
-          b_s = 0;
+        for (int q = 0; q < CB; ++q)   // row id x bytes per row + this lane's column bytes, one instruction
+          asm("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(off[q]) : "v"(rid[q]), "s"(ldb24), "v"(ld_col[q]));
+#pragma unroll
+        for (int q = 0; q < CB; ++q) dma16(p.B, off[q], b_lds + q * (NP * 1024));
+        b_lds = b_lds + B_BYTES == lds0 + PJ * 1024 + NS * B_BYTES ? lds0 + PJ * 1024 : b_lds + B_BYTES;
+        if (--b_left == 0) {
+          b_left = p.steps;
           if (++b_t < tw.count) set_tile(b_t);
         }
-      };
-      auto rowids_of = [&](int g) {
-        return *reinterpret_cast<const int*>(smem + RIDRING + (g % kRidSlots) * (kStepRows * 4) + (lane & 31) * 4);
       };
       // loads this producer issued in each of the last PB-1 iterations (oldest first)
       int issued[PB > 1 ? PB - 1 : 1] = {};
@@ -323,14 +326,18 @@ __global__ void __launch_bounds__((NC + kProducers) * 64, 3) spmm_kernel(SpmmPar
       for (int i = -PA; i < 0; ++i) {
         int n = 0;
         if (i + PA < G) { next_record(); n += CA; }
-        if (i + PB >= 0 && i + PB < G) { next_rows(rowids_of(i + PB)); n += CB; }
+        if (i + PB >= 0 && i + PB < G) { read_rowids(); next_rows(); n += CB; }
         remember(n);
       }
-      int ridv = PB < G ? rowids_of(PB) : 0;       // row ids of the k-step issued next
-      int c_s = 0, c_t = 0;                        // k-step inside the tile / tile the consumers are on
-      for (int g = 0; g < G; ++g) {
-        wait_loads<(PB - 1) * L>(outstanding_after_step());
-        if (p.pad_row0 < kStepRows && c_s == ((p.serpentine && (c_t & 1)) ? 0 : p.steps - 1)) {
+      const bool ragged = p.pad_row0 < kStepRows;  // K/M is not a multiple of 8
+      int c_left = p.steps, c_t = 0;               // k-steps left in the tile the consumers are on / that tile
+      // One iteration.  STEADY: all three streams are inside the sequence and have been for PB
+      // iterations, so the loads outstanding after those of step g are a compile-time count.
+      auto iteration = [&](int g, auto steady_const) {
+        constexpr bool STEADY = decltype(steady_const)::value;
+        if constexpr (STEADY) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((PB - 1) * L) : "memory");
+        else wait_loads<(PB - 1) * L>(outstanding_after_step());
+        if (ragged && c_left == ((p.serpentine && (c_t & 1)) ? p.steps : 1)) {
           // The last k-step of a tile when K/M is not a multiple of 8: its trailing groups do not
           // exist.  Their values are zero, but 0 x Inf is not, so the rows gathered for them (row 0
           // of B, a valid address that keeps the load count exact) are overwritten with zeros once
@@ -344,17 +351,23 @@ __global__ void __launch_bounds__((NC + kProducers) * 64, 3) spmm_kernel(SpmmPar
         } else barrier_only();
         // after barrier g the consumers are done with stage g-D and record g-D
         int n = 0;
+        const bool rows = STEADY || g + PB < G;
+        if (rows) read_rowids();
         if constexpr (CR != 0)
-          if (g + RA < G) { next_rowids(); n += 1; }
-        if (g + PA < G) { next_record(); n += CA; }
-        if (g + PB < G) {
-          next_rows(ridv);
-          n += CB;
-          if (g + PB + 1 < G) ridv = rowids_of(g + PB + 1);
-        }
-        remember(n);
-        if (++c_s == p.steps) { c_s = 0; ++c_t; barrier_only(); }
+          if (STEADY || g + RA < G) { next_rowids(); n += 1; }
+        if (STEADY || g + PA < G) { next_record(); n += CA; }
+        if (rows) { next_rows(); n += CB; }
+        if constexpr (!STEADY) remember(n);
+        if (--c_left == 0) { c_left = p.steps; ++c_t; barrier_only(); }
+      };
+      int g = 0;
+      for (; g < G && g < PB; ++g) iteration(g, std::false_type{});
+      if (g + RA < G) {
+        for (; g + RA < G; ++g) iteration(g, std::true_type{});
+#pragma unroll
+        for (int k = 0; k < PB - 1; ++k) issued[k] = L;   // what the steady iterations issued
       }
+      for (; g < G; ++g) iteration(g, std::false_type{});
     };
     switch (wave - NC) {
       case 0: produce(std::integral_constant<int, 0>{}); break;
