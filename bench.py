@@ -76,6 +76,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="skip the table of the other workloads")
+    ap.add_argument("--all-sweep-points", action="store_true",
+                    help="the table holds all 36 points of the sparsity sweep (C = 256, 2048, 8192) instead of the C = 2048 column")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--settle", type=int, default=400,
                     help="untimed launches of the product kernel before the warm-up (profiling runs use fewer)")
@@ -235,7 +237,8 @@ def main():
     # ------------------------------------------------------------------ the other workloads
     if not args.no_configs and args.workload == "gpt3" and args.variant < 0:
         names = ["tiny", "bert_base", "bert_large"]
-        names += [f"sweep_v{v}_m{m}_c2048" for v in inputs.SWEEP_V for m in inputs.SWEEP_M]
+        sweep_c = inputs.SWEEP_C if args.all_sweep_points else (2048,)
+        names += [f"sweep_v{v}_m{m}_c{c}" for c in sweep_c for v in inputs.SWEEP_V for m in inputs.SWEEP_M]
         names += [f"colloc_k{k}_m{m}" for k in (4000, 16000) for m in (10, 20, 40, 100)]
         table = []
         for name in names:

@@ -304,6 +304,35 @@ def venom_linear_static(h: Handle, X, out, bias=None, activation="none", stream=
     return out
 
 
+class Spmm:
+    """The layer object of the paper's end-to-end section (its module listing): built once from a
+    dense weight, a mask and a bias, it holds the compressed handle and is called like the linear
+    layer it replaces, `y = layer(x)` with x tokens x K and y tokens x R.  Holds state only; every
+    call is one venom_linear (the scratch for the transposed activations is kept between calls)."""
+
+    def __init__(self, weight, mask, bias=None, V=128, N=2, M=8, activation="none"):
+        self.handle = venom_compress(weight, mask, V, N, M)
+        self.bias = bias
+        self.activation = activation
+        self._scratch = None
+
+    @classmethod
+    def from_dense(cls, weight, bias=None, V=128, N=2, M=8, activation="none"):
+        """Magnitude-prunes `weight` to V:N:M on the GPU (venom_prune), then compresses it."""
+        mask, _, _ = venom_prune(weight, V, N, M)
+        return cls(weight, mask, bias, V, N, M, activation)
+
+    def __call__(self, x, out=None, out_dtype=None, stream=None):
+        import torch
+        need = c_size_t(0)
+        st = lib().venom_linear_scratch_bytes(self.handle.ptr, x.shape[0], byref(need))
+        if st != VENOM_OK:
+            raise VenomError(st, "venom_linear_scratch_bytes")
+        if self._scratch is None or self._scratch.numel() < need.value or self._scratch.device != x.device:
+            self._scratch = torch.empty(max(need.value, 16), dtype=torch.uint8, device=x.device)
+        return venom_linear(self.handle, x, self.bias, self.activation, out, out_dtype, self._scratch, stream)
+
+
 def venom_get_info(h: Handle):
     R, K = c_int64(), c_int64()
     V, N, M = c_int(), c_int(), c_int()

@@ -70,3 +70,22 @@ def test_argument_errors():
     with pytest.raises(binding.VenomError) as e:
         binding.venom_linear(h, X_d, scratch=torch.empty(64, dtype=torch.uint8, device=DEV))
     assert e.value.status == binding.VENOM_ERR_WORKSPACE
+
+
+def test_layer_object_prunes_compresses_and_matches_the_oracle():
+    """The layer object (paper's end-to-end section): dense weight -> magnitude pruning -> V:N:M ->
+    y = act(x W^T + b), two calls with different token counts through the same object."""
+    R, K, V, M = 256, 512, 128, 16
+    rng = np.random.default_rng(77)
+    W = rng.standard_normal((R, K)).astype(np.float16)
+    bias = rng.standard_normal(R).astype(np.float16)
+    layer = binding.Spmm.from_dense(torch.from_numpy(W).to(DEV), bias=torch.from_numpy(bias).to(DEV), V=V, N=2, M=M,
+                                    activation="gelu")
+    mask, _, _ = o.prune(W.view(np.uint16), V, M)
+    ov, oc, om = o.compress(W.view(np.uint16), mask, V, M)
+    for T in (264, 72):
+        X = rng.standard_normal((T, K)).astype(np.float16)
+        Y = layer(torch.from_numpy(X).to(DEV))
+        Ys, Ey = o.linear_fp64(ov, oc, om, R, K, V, M, X.view(np.uint16), bias.view(np.uint16), "gelu")
+        ok, info = o.accept(Y.double().cpu().numpy(), Ys, Ey)
+        assert ok, (T, info)
