@@ -475,10 +475,10 @@ __global__ void __launch_bounds__((NC + kProducers) * 64, 3) spmm_kernel(SpmmPar
 
       // ---- stage 3: registers -> (LDS) -> global.  Accumulator element v of a 32x32 tile sits
       // at row 8*(v/4) + 4*(lane/32) + v%4, column lane%32.
-      // everything below is per-tile work: keep its index arithmetic from being hoisted out of the
-      // tile loop, where it would sit in registers the k-loop needs
-      int ln = lane;
-      asm volatile("" : "+v"(ln));
+      // everything below is per-tile work: its index arithmetic starts from a lane id computed here,
+      // so that none of it is hoisted out of the tile loop into registers the k-loop needs
+      int ln;
+      asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(ln));
       int ct, br;
       tw.locate(p, t, ct, br);
       const int64_t row0 = (int64_t)br * RT * 32;
