@@ -14,6 +14,7 @@ is stated on.  Prints ONE JSON line:
   dense_gemm       torch.matmul (hipBLASLt) of the same R x K x C on the same GPU, same loop
   measured_peak    the 2:4 matrix instruction alone (register operands), timed here: the rate the
                    GPU sustains at the clock it holds under that load
+  hbm_calibration  plain fill / sum / copy of 1 GiB on the same GPU: the HBM rates it sustains
   configs          the other workloads (tiny, BERT-base, BERT-large, the C = 2048 column of the
                    sparsity sweep, the 1024 x K x 4096 column-loc ablation shape): hot and, where
                    HBM-bound, cold (B and C rotated through more memory than the caches hold)
@@ -189,6 +190,19 @@ def main():
     _, p_avg, _, _ = timed(lambda: binding.venom_probe_smfmac_rate(probe_iters, sink), 20, 3)
     measured_peak = probe_iters * 8 * 32768.0 * 16 * cus / (p_avg * 1e-3) / 1e12
 
+    # what the memory system of this GPU sustains for plain streaming kernels (context for the
+    # bandwidth-bound rows: the published 8 TB/s is not reached by any access pattern)
+    cal = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()      # 1 GiB
+    cal2 = torch.empty_like(cal)
+    _, _, w_med, _ = timed(lambda: cal2.fill_(1.0), 10, 2)
+    _, _, c_med, _ = timed(lambda: cal2.copy_(cal), 10, 2)
+    _, _, r_med, _ = timed(lambda: torch.sum(cal), 10, 2)
+    hbm_cal = {"bytes": 1 << 30, "write_GBs": round((1 << 30) / (w_med * 1e-3) / 1e9, 1),
+               "read_GBs": round((1 << 30) / (r_med * 1e-3) / 1e9, 1),
+               "copy_GBs_read_plus_write": round((2 << 30) / (c_med * 1e-3) / 1e9, 1),
+               "kind": "torch fill_ / sum / copy_ on 1 GiB fp32 tensors, median of 10"}
+    del cal, cal2
+
     step = lambda: binding.venom_spmm(h, B_d, out=C_d, variant=args.variant)
     # The power management needs about a hundred launches (25 ms) of THIS kernel to settle on its
     # clock: the first launches after any change of load run 10-20 % slower, whatever ran before.
@@ -229,6 +243,7 @@ def main():
                           "kind": "v_smfmac_f32_32x32x32_f16 on register operands, 16 waves per compute unit, "
                                   "pseudo-random values; useful FLOP = half of the dense-equivalent count"},
     }
+    out["hbm_calibration"] = hbm_cal
     if dense_entry is not None:
         dense_entry["speedup_of_spmm"] = round(dense_entry["ms"] / ms_avg, 3)
         dense_entry["ideal_speedup"] = M / N
