@@ -131,7 +131,11 @@ struct TileWalk {
 };
 
 // MODE 0: the plain product; 1: fused bias / activation; 2: the same with C written transposed
-// (token-major).  Separate instantiations: the plain kernel carries none of the epilogue code.
+// (token-major), straight from the accumulators; 3: token-major fp16 through LDS with 16-byte
+// stores (needs the output and its leading dimension 16-byte aligned).  Separate instantiations:
+// the plain kernel carries none of the epilogue code, and one kernel holding both token-major
+// paths behind a run-time branch does not compile (the compiler then keeps the producers' scalar
+// operands in vector registers).
 // NS: stages of the B ring; NA: records in the A ring.
 // D: barriers after which a consumed stage returns to the producers.  The consumers read stage g
 // between barriers g and g+1 but use what they read only after barrier g+1.  D = 2: they do not
@@ -519,34 +523,88 @@ __global__ void __launch_bounds__((NC + kProducers) * 64, 3) spmm_kernel(SpmmPar
             }
         }
       };
-      if constexpr (MODE == 2) {
-        // Token-major output Y[token][feature] = C transposed: a ln owns one column of C (a
-        // token) and, per 32-row tile, four runs of 4 consecutive rows (features): each run is one
-        // 8-byte (fp16) or 16-byte (fp32) store straight from the accumulators; the two half-waves
-        // write neighbouring runs, the tiles of a block row continue the same 2*V bytes of a token.
+      if constexpr (MODE >= 2) {
+        // Token-major output Y[token][feature] = C transposed: a lane owns one column of C (a token)
+        // and, per 32-row tile, four runs of 4 consecutive rows (features).
+        auto direct = [&]() {
+          // each run is one 8-byte (fp16) or 16-byte (fp32) store straight from the accumulators;
+          // the two half-waves write neighbouring runs
 #pragma unroll
-        for (int tr = 0; tr < RT; ++tr) {
-          finish(tr);
+          for (int tr = 0; tr < RT; ++tr) {
+            finish(tr);
 #pragma unroll
-          for (int tc = 0; tc < CT; ++tc) {
-            const int64_t tok = col0 + tc * 32 + (ln & 31);
-            if (tok < p.Ccols) {
+            for (int tc = 0; tc < CT; ++tc) {
+              const int64_t tok = col0 + tc * 32 + (ln & 31);
+              if (tok < p.Ccols) {
 #pragma unroll
-              for (int q = 0; q < 4; ++q) {
-                const int64_t feat = row0 + tr * 32 + 8 * q + 4 * (ln >> 5);
-                if constexpr (OUT_F32) {
-                  typedef float f32x4 __attribute__((ext_vector_type(4)));
-                  const f32x4 o = {acc[tr][tc][4 * q], acc[tr][tc][4 * q + 1], acc[tr][tc][4 * q + 2], acc[tr][tc][4 * q + 3]};
-                  *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.C) + tok * p.ldc + feat) = o;
-                } else {
-                  const half4 o = {(_Float16)acc[tr][tc][4 * q], (_Float16)acc[tr][tc][4 * q + 1],
-                                   (_Float16)acc[tr][tc][4 * q + 2], (_Float16)acc[tr][tc][4 * q + 3]};
-                  *reinterpret_cast<half4*>(reinterpret_cast<_Float16*>(p.C) + tok * p.ldc + feat) = o;
+                for (int q = 0; q < 4; ++q) {
+                  const int64_t feat = row0 + tr * 32 + 8 * q + 4 * (ln >> 5);
+                  if constexpr (OUT_F32) {
+                    typedef float f32x4 __attribute__((ext_vector_type(4)));
+                    const f32x4 o = {acc[tr][tc][4 * q], acc[tr][tc][4 * q + 1], acc[tr][tc][4 * q + 2], acc[tr][tc][4 * q + 3]};
+                    *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.C) + tok * p.ldc + feat) = o;
+                  } else {
+                    const half4 o = {(_Float16)acc[tr][tc][4 * q], (_Float16)acc[tr][tc][4 * q + 1],
+                                     (_Float16)acc[tr][tc][4 * q + 2], (_Float16)acc[tr][tc][4 * q + 3]};
+                    *reinterpret_cast<half4*>(reinterpret_cast<_Float16*>(p.C) + tok * p.ldc + feat) = o;
+                  }
                 }
               }
             }
+            __builtin_amdgcn_sched_barrier(0);
           }
-          __builtin_amdgcn_sched_barrier(0);
+        };
+        if constexpr (OUT_F32 || MODE == 2) {
+          direct();
+        } else {
+          // fp16: the 8-byte runs of FT tile rows go through this wave's 4 KB of the drained stage
+          // as [token][32*FT features] and leave as 16-byte stores, 64*FT contiguous bytes per
+          // token (a full 128-byte line when the block height allows pairs of tile rows).  The
+          // 8-byte slots of a staged row are XOR-swizzled by the token so that neighbouring tokens,
+          // whose rows lie 64*FT bytes apart, use different banks.
+          constexpr int FT = RT % 2 == 0 ? 2 : 1;  // 32-row tiles per pass
+          constexpr int RB = 64 * FT;              // bytes of a staged token row
+          constexpr int LPT = RB / 16;             // lanes (16-byte chunks) per token row
+          constexpr int TPI = 64 / LPT;            // tokens per wave-wide read
+          constexpr int SH = FT == 2 ? 1 : 2;      // tokens 2^SH apart share a bank group
+          char* stg = const_cast<char*>(sb) + wave * 4096;
+          _Float16* Y = reinterpret_cast<_Float16*>(p.C);
+          const int h = ln >> 5;
+#pragma unroll
+          for (int trg = 0; trg < RT / FT; ++trg) {
+#pragma unroll
+            for (int trr = 0; trr < FT; ++trr) finish(trg * FT + trr);
+#pragma unroll
+            for (int ps = 0; ps < FT; ++ps) {      // FT = 2: one column tile per pass; FT = 1: both in one pass
+#pragma unroll
+              for (int tc = (FT == 2 ? ps : 0); tc < (FT == 2 ? ps + 1 : CT); ++tc) {
+                const int t = (FT == 2 ? 0 : tc * 32) + (ln & 31);
+                const int sw = 2 * ((t >> SH) & (LPT - 1));
+#pragma unroll
+                for (int trr = 0; trr < FT; ++trr)
+#pragma unroll
+                  for (int q = 0; q < 4; ++q) {
+                    const int tr = trg * FT + trr;
+                    const half4 o = {(_Float16)acc[tr][tc][4 * q], (_Float16)acc[tr][tc][4 * q + 1],
+                                     (_Float16)acc[tr][tc][4 * q + 2], (_Float16)acc[tr][tc][4 * q + 3]};
+                    const int slot = trr * 8 + 2 * q + h;
+                    *reinterpret_cast<half4*>(stg + t * RB + ((slot ^ sw) * 8)) = o;
+                  }
+              }
+#pragma unroll
+              for (int i = 0; i < (64 / FT) / TPI; ++i) {
+                const int tt = i * TPI + ln / LPT, c = ln % LPT;
+                const uint4 val = *reinterpret_cast<const uint4*>(stg + tt * RB + ((c ^ ((tt >> SH) & (LPT - 1))) * 16));
+                const int64_t tok = col0 + (FT == 2 ? ps * 32 : 0) + tt;
+                if (tok < p.Ccols) {
+                  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+                  const u32x4 v4 = {val.x, val.y, val.z, val.w};
+                  *reinterpret_cast<u32x4*>(Y + tok * p.ldc + row0 + trg * FT * 32 + c * 8) = v4;
+                }
+              }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
         }
       } else if constexpr (OUT_F32) {
         float* Cf = reinterpret_cast<float*>(p.C);
@@ -620,7 +678,7 @@ struct Variant {
   int bsc;     // columns per workgroup
   int threads;
   int lds;     // dynamic LDS bytes
-  void (*fn[2][3])(SpmmParams);   // [fp32 output][mode]
+  void (*fn[2][4])(SpmmParams);   // [fp32 output][mode]
 };
 
 template <int VT, int NC, int NS, int NA>
@@ -631,9 +689,9 @@ constexpr int lds_bytes() {   // B ring, A ring, row-id ring (the output staging
 #define VARIANT(NAME, VT, NC, NS, NA, D)                                                                  \
   { NAME, (VT) * 32, 64 * (NC), 64 * ((NC) + kProducers), lds_bytes<VT, NC, NS, NA>(),                     \
     { { spmm_kernel<VT, NC, NS, NA, D, false, 0>, spmm_kernel<VT, NC, NS, NA, D, false, 1>,               \
-        spmm_kernel<VT, NC, NS, NA, D, false, 2> },                                                     \
+        spmm_kernel<VT, NC, NS, NA, D, false, 2>, spmm_kernel<VT, NC, NS, NA, D, false, 3> },             \
       { spmm_kernel<VT, NC, NS, NA, D, true, 0>, spmm_kernel<VT, NC, NS, NA, D, true, 1>,                 \
-        spmm_kernel<VT, NC, NS, NA, D, true, 2> } } }
+        spmm_kernel<VT, NC, NS, NA, D, true, 2>, spmm_kernel<VT, NC, NS, NA, D, true, 2> } } }
 
 #ifndef VENOM_D
 #define VENOM_D 2
@@ -719,18 +777,20 @@ venom_status_t launch_spmm(const venom_handle& h, const void* B, int64_t ldb, in
   const unsigned grid = (unsigned)(wg_per_xcd * kNumXcd);
   // a workgroup numbers the k-steps of all its tiles with one 32-bit counter
   if ((p.per_xcd + wg_per_xcd - 1) / wg_per_xcd * L.steps >= ((int64_t)1 << 30)) return VENOM_ERR_UNSUPPORTED;
-  const int epi = tokens_major ? 2 : ((bias != nullptr || act != VENOM_ACT_NONE) ? 1 : 0);
+  // token-major fp16 output takes the staged path when 16-byte stores are possible
+  const bool wide = tokens_major && c_dtype == 0 && reinterpret_cast<uintptr_t>(C) % 16 == 0 && ldc % 8 == 0;
+  const int epi = tokens_major ? (wide ? 3 : 2) : ((bias != nullptr || act != VENOM_ACT_NONE) ? 1 : 0);
   auto fn = var.fn[c_dtype == 1 ? 1 : 0][epi];
   if (var.lds > 64 * 1024) {
     // opting in to more than 64 KB of dynamic LDS is a per-function attribute (set once per device)
     // (two threads racing here both set the same attribute: harmless)
-    static std::atomic<bool> opted_in[kNumVariants][6][kMaxDevices] = {};
+    static std::atomic<bool> opted_in[kNumVariants][8][kMaxDevices] = {};
     const bool cached = dev >= 0 && dev < kMaxDevices;
-    if (!cached || !opted_in[variant][3 * c_dtype + epi][dev].load(std::memory_order_acquire)) {
+    if (!cached || !opted_in[variant][4 * c_dtype + epi][dev].load(std::memory_order_acquire)) {
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
                               var.lds) != hipSuccess)
         return VENOM_ERR_HIP;
-      if (cached) opted_in[variant][3 * c_dtype + epi][dev].store(true, std::memory_order_release);
+      if (cached) opted_in[variant][4 * c_dtype + epi][dev].store(true, std::memory_order_release);
     }
   }
   hipLaunchKernelGGL(fn, dim3(grid), dim3(var.threads), var.lds, st, p);
