@@ -14,7 +14,7 @@ is stated on.  Prints ONE JSON line:
   dense_gemm       torch.matmul (hipBLASLt) of the same R x K x C on the same GPU, same loop
   measured_peak    the 2:4 matrix instruction alone (register operands), timed here: the rate the
                    GPU sustains at the clock it holds under that load
-  hbm_calibration  plain fill / sum / copy of 1 GiB on the same GPU: the HBM rates it sustains
+  hbm_calibration  plain fill / copy of 1 GiB on the same GPU: the HBM rates linear streams sustain
   configs          the other workloads (tiny, BERT-base, BERT-large, the C = 2048 column of the
                    sparsity sweep, the 1024 x K x 4096 column-loc ablation shape): hot and, where
                    HBM-bound, cold (B and C rotated through more memory than the caches hold)
@@ -196,11 +196,9 @@ def main():
     cal2 = torch.empty_like(cal)
     _, _, w_med, _ = timed(lambda: cal2.fill_(1.0), 10, 2)
     _, _, c_med, _ = timed(lambda: cal2.copy_(cal), 10, 2)
-    _, _, r_med, _ = timed(lambda: torch.sum(cal), 10, 2)
     hbm_cal = {"bytes": 1 << 30, "write_GBs": round((1 << 30) / (w_med * 1e-3) / 1e9, 1),
-               "read_GBs": round((1 << 30) / (r_med * 1e-3) / 1e9, 1),
                "copy_GBs_read_plus_write": round((2 << 30) / (c_med * 1e-3) / 1e9, 1),
-               "kind": "torch fill_ / sum / copy_ on 1 GiB fp32 tensors, median of 10"}
+               "kind": "torch fill_ / copy_ on 1 GiB fp32 tensors (linear streams), median of 10"}
     del cal, cal2
 
     step = lambda: binding.venom_spmm(h, B_d, out=C_d, variant=args.variant)
