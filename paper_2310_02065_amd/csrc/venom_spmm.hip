@@ -693,14 +693,12 @@ constexpr int lds_bytes() {   // B ring, A ring, row-id ring (the output staging
       { spmm_kernel<VT, NC, NS, NA, D, true, 0>, spmm_kernel<VT, NC, NS, NA, D, true, 1>,                 \
         spmm_kernel<VT, NC, NS, NA, D, true, 2>, spmm_kernel<VT, NC, NS, NA, D, true, 2> } } }
 
-#ifndef VENOM_D
-#define VENOM_D 2
-#endif
+constexpr int kD = 2;   // barriers between the hand-over of a stage and its return (1 and 2 measure the same)
 static const Variant kVariants[] = {
-    VARIANT("v128_c512", 4, 8, 4, 6, VENOM_D), VARIANT("v128_c256", 4, 4, 6, 10, VENOM_D), VARIANT("v128_c128", 4, 2, 8, 10, VENOM_D),
-    VARIANT("v96_c512", 3, 8, 4, 8, VENOM_D),  VARIANT("v96_c256", 3, 4, 6, 10, VENOM_D), VARIANT("v96_c128", 3, 2, 8, 10, VENOM_D),
-    VARIANT("v64_c512", 2, 8, 4, 10, VENOM_D), VARIANT("v64_c256", 2, 4, 6, 10, VENOM_D), VARIANT("v64_c128", 2, 2, 8, 10, VENOM_D),
-    VARIANT("v32_c512", 1, 8, 4, 10, VENOM_D), VARIANT("v32_c256", 1, 4, 6, 10, VENOM_D), VARIANT("v32_c128", 1, 2, 8, 10, VENOM_D),
+    VARIANT("v128_c512", 4, 8, 4, 6, kD), VARIANT("v128_c256", 4, 4, 6, 10, kD), VARIANT("v128_c128", 4, 2, 8, 10, kD),
+    VARIANT("v96_c512", 3, 8, 4, 8, kD),  VARIANT("v96_c256", 3, 4, 6, 10, kD), VARIANT("v96_c128", 3, 2, 8, 10, kD),
+    VARIANT("v64_c512", 2, 8, 4, 10, kD), VARIANT("v64_c256", 2, 4, 6, 10, kD), VARIANT("v64_c128", 2, 2, 8, 10, kD),
+    VARIANT("v32_c512", 1, 8, 4, 10, kD), VARIANT("v32_c256", 1, 4, 6, 10, kD), VARIANT("v32_c128", 1, 2, 8, 10, kD),
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
