@@ -15,6 +15,8 @@ is stated on.  Prints ONE JSON line:
   measured_peak    the 2:4 matrix instruction alone (register operands), timed here: the rate the
                    GPU sustains at the clock it holds under that load
   hbm_calibration  plain fill / copy of 1 GiB on the same GPU: the HBM rates linear streams sustain
+  calls            the other entry points on the headline matrix: fused bias / GELU, the token-major
+                   layer call, magnitude pruning, compression
   configs          the other workloads (tiny, BERT-base, BERT-large, the C = 2048 column of the
                    sparsity sweep, the 1024 x K x 4096 column-loc ablation shape): hot and, where
                    HBM-bound, cold (B and C rotated through more memory than the caches hold)
@@ -268,6 +270,52 @@ def main():
         dense_entry["speedup_of_spmm"] = round(dense_entry["ms"] / ms_avg, 3)
         dense_entry["ideal_speedup"] = M / N
         out["dense_gemm"] = dense_entry
+
+    # ------------------------------------------------------------------ the other calls on the headline matrix
+    if not args.no_configs and args.variant < 0:
+        n = 100
+        bias_d = torch.randn(R, device=dev, dtype=torch.float32).to(torch.float16)
+        X_d = B_d.t().contiguous()                       # tokens x K, as a linear layer holds its activations
+        Y_d = torch.empty((C, R), dtype=torch.float16, device=dev)
+        scratch = torch.empty(max(2 * K * C, 16), dtype=torch.uint8, device=dev)
+        calls = []
+
+        def call_entry(name, fn, bytes_moved=None):
+            _, _, med, _ = timed(fn, n, 20)
+            e = {"call": name, "ms": round(med, 5)}
+            if bytes_moved is not None:
+                e.update({"algorithmic_bytes": int(bytes_moved), "GBs": round(bytes_moved / (med * 1e-3) / 1e9, 1),
+                          "frac_of_hbm_peak": round(bytes_moved / (med * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)})
+            else:
+                e["useful_tflops"] = round(useful_flop / (med * 1e-3) / 1e12, 2)
+            calls.append(e)
+
+        call_entry("venom_spmm", step)
+        call_entry("venom_spmm_bias_act: bias", lambda: binding.venom_spmm(h, B_d, out=C_d, bias=bias_d))
+        call_entry("venom_spmm_bias_act: bias + GELU", lambda: binding.venom_spmm(h, B_d, out=C_d, bias=bias_d, activation="gelu"))
+        call_entry("venom_linear (token-major in and out, transpose of the activations included)",
+                   lambda: binding.venom_linear(h, X_d, out=Y_d, scratch=scratch))
+        call_entry("venom_linear: bias + GELU",
+                   lambda: binding.venom_linear(h, X_d, out=Y_d, scratch=scratch, bias=bias_d, activation="gelu"))
+        del X_d, Y_d, scratch
+        # once-per-matrix calls on a dense matrix of the same shape: magnitude pruning, compression
+        g = torch.Generator(device=dev).manual_seed(w["seed"])
+        W_d = (torch.randn((R, K), generator=g, device=dev, dtype=torch.float32) * 0.02).to(torch.float16)
+        pruned = binding.venom_prune(W_d, V, N, M)
+        call_entry("venom_prune (dense fp16 in, mask out)", lambda: binding.venom_prune(W_d, V, N, M), 3.0 * R * K)
+        ws_keep = []
+
+        def compress_once():
+            ws_keep.clear()
+            ws_keep.append(binding.venom_compress(W_d, pruned[0], V, N, M))
+        _, _, c_med, _ = timed(compress_once, 10, 2)
+        cb = 3.0 * R * K + 2.0 * (4.5 * R * (K // M)) + 8.0 * (R // V) * (K // M)   # A + mask in, canonical + packed arrays out
+        calls.append({"call": "venom_compress (dense + mask in, canonical and packed arrays out; one host round trip)",
+                      "ms": round(c_med, 5), "algorithmic_bytes": int(cb), "GBs": round(cb / (c_med * 1e-3) / 1e9, 1),
+                      "frac_of_hbm_peak": round(cb / (c_med * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)})
+        ws_keep.clear()
+        del W_d, pruned, bias_d
+        out["calls"] = calls
 
     # ------------------------------------------------------------------ the other workloads
     if not args.no_configs and args.workload == "gpt3" and args.variant < 0:
