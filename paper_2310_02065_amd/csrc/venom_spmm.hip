@@ -490,7 +490,7 @@ __global__ void __launch_bounds__((NC + kProducers) * 64, 3) spmm_kernel(SpmmPar
       // fused epilogue (the layer's bias, one per output row, then the activation), in fp32 on
       // the accumulators, one 32-row tile at a time right before it is stored: a ln holds rows
       // 8j + 4*(ln/32) + 0..3 of the tile
-      auto finish = [&](int tr) {
+      auto finish = [&](int tr, int tc_lo = 0, int tc_hi = CT) {   // column tiles tc_lo .. tc_hi-1 of tile row tr
         if constexpr (!EPI) return;                // the plain product compiles without any of this
         if (p.bias) {
 #pragma unroll
@@ -499,7 +499,7 @@ __global__ void __launch_bounds__((NC + kProducers) * 64, 3) spmm_kernel(SpmmPar
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-              for (int tc = 0; tc < CT; ++tc) acc[tr][tc][4 * j + i] += (float)b4[i];
+              for (int tc = tc_lo; tc < tc_hi; ++tc) acc[tr][tc][4 * j + i] += (float)b4[i];
             __builtin_amdgcn_sched_barrier(0);
           }
         }
@@ -507,7 +507,7 @@ __global__ void __launch_bounds__((NC + kProducers) * 64, 3) spmm_kernel(SpmmPar
         // temporaries would push accumulators out of registers, for the whole kernel)
         if (p.act == VENOM_ACT_GELU) {
 #pragma unroll
-          for (int tc = 0; tc < CT; ++tc)
+          for (int tc = tc_lo; tc < tc_hi; ++tc)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
               acc[tr][tc][v] = gelu_by_definition(acc[tr][tc][v]);
@@ -515,7 +515,7 @@ __global__ void __launch_bounds__((NC + kProducers) * 64, 3) spmm_kernel(SpmmPar
             }
         } else if (p.act == VENOM_ACT_GELU_TANH) {
 #pragma unroll
-          for (int tc = 0; tc < CT; ++tc)
+          for (int tc = tc_lo; tc < tc_hi; ++tc)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
               acc[tr][tc][v] = gelu_tanh_form(acc[tr][tc][v]);
@@ -573,9 +573,12 @@ __global__ void __launch_bounds__((NC + kProducers) * 64, 3) spmm_kernel(SpmmPar
 #pragma unroll
           for (int trg = 0; trg < RT / FT; ++trg) {
 #pragma unroll
-            for (int trr = 0; trr < FT; ++trr) finish(trg * FT + trr);
-#pragma unroll
             for (int ps = 0; ps < FT; ++ps) {      // FT = 2: one column tile per pass; FT = 1: both in one pass
+#pragma unroll
+              for (int trr = 0; trr < FT; ++trr) {   // the epilogue of exactly what this pass stores
+                if constexpr (FT == 2) finish(trg * FT + trr, ps, ps + 1);
+                else finish(trg * FT + trr);
+              }
 #pragma unroll
               for (int tc = (FT == 2 ? ps : 0); tc < (FT == 2 ? ps + 1 : CT); ++tc) {
                 const int t = (FT == 2 ? 0 : tc * 32) + (ln & 31);
