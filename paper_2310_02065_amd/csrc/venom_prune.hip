@@ -35,16 +35,17 @@ __device__ __forceinline__ unsigned magnitude_key(uint16_t bits) {
 }
 
 // One workgroup per (block row b, chunk of `gpw` groups): V rows x gpw*M columns.
-//   phase 1: column masses into LDS (64-bit integer adds), the block's total mass, mask zero fill.
-//            A thread owns 8 neighbouring columns (one 16-byte load, one 8-byte mask store) and a
-//            slice of the rows, sums in registers and adds once per column; columns past the last
-//            multiple of 8 and unaligned inputs take the element-wise loop.
+//   phase 1: column masses into LDS (64-bit integer adds), the block's total mass.  A thread owns
+//            8 neighbouring columns (one 16-byte load) and a slice of the rows, sums in registers
+//            and adds once per column; columns past the last multiple of 8 and unaligned inputs
+//            take the element-wise loop.
 //   phase 2: one thread per group picks the 4 columns: largest mass first, smaller index on ties,
 //            then sorted ascending
 //   phase 3: one thread per (row, group): the 2 largest magnitudes among the 4, smaller position on
-//            ties; sets the two mask bytes
+//            ties; writes the M mask bytes of its row and group, two of them 1, with the widest
+//            stores the alignment allows (`mask_word`: 16, 8, 4 or 1 bytes), so the mask is written once
 __global__ void __launch_bounds__(256) prune_kernel(const uint16_t* __restrict__ A, int64_t lda, int V, int M,
-                                                    int64_t G, int gpw, int vec_ok, uint8_t* __restrict__ mask,
+                                                    int64_t G, int gpw, int vec_ok, int mask_word, uint8_t* __restrict__ mask,
                                                     int64_t ldm, unsigned long long* __restrict__ kept_mass,
                                                     unsigned long long* __restrict__ total_mass) {
   __shared__ unsigned long long mass[kPruneMaxCols];
@@ -76,7 +77,6 @@ __global__ void __launch_bounds__(256) prune_kernel(const uint16_t* __restrict__
             m8[2 * e] += magnitude_units((uint16_t)ws[e]);
             m8[2 * e + 1] += magnitude_units((uint16_t)(ws[e] >> 16));
           }
-          *reinterpret_cast<uint2*>(mask + (b * V + v) * ldm + g0 * M + 8 * u) = make_uint2(0, 0);
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -91,7 +91,6 @@ __global__ void __launch_bounds__(256) prune_kernel(const uint16_t* __restrict__
   for (int64_t i = tid; i < (int64_t)V * tail; i += blockDim.x) {
     const int v = (int)(i / tail), c = tail0 + (int)(i % tail);
     const unsigned long long m = magnitude_units(A[(b * V + v) * lda + g0 * M + c]);
-    mask[(b * V + v) * ldm + g0 * M + c] = 0;
     if (m) atomicAdd(&mass[c], m);
     my_total += m;
   }
@@ -113,7 +112,7 @@ __global__ void __launch_bounds__(256) prune_kernel(const uint16_t* __restrict__
       for (int j = i; j > 0 && s[j - 1] > s[j]; --j) { const int t = s[j]; s[j] = s[j - 1]; s[j - 1] = t; }
     for (int k = 0; k < kSelCols; ++k) sel[tid][k] = s[k];
   }
-  __syncthreads();   // also orders the zero fill of the mask before the ones below
+  __syncthreads();
   unsigned long long my_kept = 0;
   for (int i = tid; i < V * ng; i += blockDim.x) {
     const int v = i / ng, t = i % ng;
@@ -126,8 +125,28 @@ __global__ void __launch_bounds__(256) prune_kernel(const uint16_t* __restrict__
     int p1 = p0 == 0 ? 1 : 0;
     for (int p = 0; p < kSelCols; ++p) if (p != p0 && key[p] > key[p1]) p1 = p;
     uint8_t* mrow = mask + (b * V + v) * ldm + (g0 + t) * M;
-    mrow[sel[t][p0]] = 1;
-    mrow[sel[t][p1]] = 1;
+    const int c0 = sel[t][p0], c1 = sel[t][p1];
+    auto word8 = [&](int j) {   // mask bytes of columns j .. j+7
+      return ((unsigned)(c0 - j) < 8u ? 1ull << (8 * (c0 - j)) : 0ull) | ((unsigned)(c1 - j) < 8u ? 1ull << (8 * (c1 - j)) : 0ull);
+    };
+    if (mask_word == 16) {
+      for (int j = 0; j < M; j += 16) {
+        const unsigned long long lo = word8(j), hi = word8(j + 8);
+        *reinterpret_cast<uint4*>(mrow + j) = make_uint4((unsigned)lo, (unsigned)(lo >> 32), (unsigned)hi, (unsigned)(hi >> 32));
+      }
+    } else if (mask_word == 8) {
+      for (int j = 0; j < M; j += 8) {
+        *reinterpret_cast<unsigned long long*>(mrow + j) = word8(j);
+      }
+    } else if (mask_word == 4) {
+      for (int j = 0; j < M; j += 4) {
+        const unsigned word = ((unsigned)(c0 - j) < 4u ? 1u << (8 * (c0 - j)) : 0u) |
+                              ((unsigned)(c1 - j) < 4u ? 1u << (8 * (c1 - j)) : 0u);
+        *reinterpret_cast<unsigned*>(mrow + j) = word;
+      }
+    } else {
+      for (int c = 0; c < M; ++c) mrow[c] = (c == c0 || c == c1) ? 1 : 0;
+    }
     my_kept += magnitude_units(w[p0]) + magnitude_units(w[p1]);
   }
   if (my_kept) atomicAdd(&wg_kept, my_kept);
@@ -148,11 +167,14 @@ hipError_t launch_prune(const uint16_t* A, int64_t lda, int64_t R, int64_t K, in
   if (gpw > kStepGroups) gpw = kStepGroups;
   if (gpw < 1) gpw = 1;
   const int64_t chunks = (G + gpw - 1) / gpw;
-  // wide accesses need every chunk of every row to start on a 16-byte (A) / 8-byte (mask) boundary
-  const int vec_ok = ((int64_t)gpw * M) % 8 == 0 && lda % 8 == 0 && ldm % 8 == 0 &&
-                     reinterpret_cast<uintptr_t>(A) % 16 == 0 && reinterpret_cast<uintptr_t>(mask) % 8 == 0;
+  // wide loads need every chunk of every row of A to start on a 16-byte boundary
+  const int vec_ok = ((int64_t)gpw * M) % 8 == 0 && lda % 8 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0;
+  // every (row, group) of the mask starts at row * ldm + group * M: the widest word that always divides that
+  const uintptr_t ma = reinterpret_cast<uintptr_t>(mask);
+  const int mask_word = (M % 16 == 0 && ldm % 16 == 0 && ma % 16 == 0) ? 16 : (M % 8 == 0 && ldm % 8 == 0 && ma % 8 == 0) ? 8
+                        : (M % 4 == 0 && ldm % 4 == 0 && ma % 4 == 0) ? 4 : 1;
   hipLaunchKernelGGL(prune_kernel, dim3((unsigned)chunks, (unsigned)Rb), dim3(256), 0, st, A, lda, V, M, G, gpw, vec_ok,
-                     mask, ldm, kept_mass, total_mass);
+                     mask_word, mask, ldm, kept_mass, total_mass);
   return hipGetLastError();
 }
 
