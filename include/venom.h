@@ -143,8 +143,10 @@ venom_status_t venom_spmm_bias_act(const venom_handle_t* h, const void* B_f16_de
  *     Y = act(X . A^T + bias),  bias one fp16 entry per output feature (R), or NULL.
  * The gather needs rows of X^T, so X is first transposed into `scratch_dev` (caller-owned device
  * memory, 16-byte aligned, at least venom_linear_scratch_bytes() bytes, overwritten); the product
- * kernel then writes Y transposed straight from its accumulators.  tokens % 8 == 0; Y and ldy
- * aligned to 4 elements; V in {32, 64, 96, 128}.  Asynchronous on `stream`, allocates nothing. */
+ * kernel then writes Y transposed itself, no second transpose pass.  tokens % 8 == 0; Y and ldy
+ * aligned to 4 elements (fp16 output is fastest with Y and ldy * 2 bytes 16-byte aligned: whole
+ * 128-byte lines per token are then stored); V in {32, 64, 96, 128}.  Asynchronous on `stream`,
+ * allocates nothing. */
 venom_status_t venom_linear_scratch_bytes(const venom_handle_t* h, int64_t tokens, size_t* bytes);
 venom_status_t venom_linear(const venom_handle_t* h, const void* X_f16_dev, int64_t ldx, int64_t tokens,
                             const void* bias_f16_dev, int activation, void* Y_dev, int64_t ldy, int y_dtype,
