@@ -22,3 +22,20 @@ def test_algorithmic_bytes_of_the_headline_workload():
     # values 4 B per (row, group), metadata 4 bits, column-loc 8 B per (block row, group), B and C once
     assert bench.algorithmic_bytes(R, K, C, V, M) == 4 * R * G + R * G // 2 + 8 * (R // V) * G + 2 * K * C + 2 * R * C
     assert abs(bench.algorithmic_bytes(R, K, C, V, M) - 337.8e6) < 0.1e6
+
+
+def test_algorithmic_bytes_count_only_the_rows_of_B_that_are_gathered():
+    """With few block rows and a large M part of B is never selected: the B term follows the expected
+    number of distinct selected rows, checked here against a count on a generated structure."""
+    sys.path.insert(0, ROOT)
+    import numpy as np
+    import bench
+    from paper_2310_02065_amd import inputs
+    R, K, C, V, M = 1024, 4000, 4096, 128, 100
+    _, mask, _ = inputs.gen_problem(R, K, 8, V, M, 1.0, seed=5)
+    used_rows = int((mask.reshape(R, K).sum(axis=0) > 0).sum())          # rows of B some block row selects
+    G = K // M
+    other = 4 * R * G + R * G // 2 + 8 * (R // V) * G + 2 * R * C
+    b_term = bench.algorithmic_bytes(R, K, C, V, M) - other
+    assert abs(b_term - 2 * used_rows * C) <= 0.05 * 2 * used_rows * C
+    assert used_rows < K // 2                                              # most of B is indeed never read
