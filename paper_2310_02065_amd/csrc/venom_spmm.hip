@@ -866,9 +866,51 @@ __global__ void __launch_bounds__(256) transpose_tokens_kernel(const uint16_t* _
   }
 }
 
+// The same with 16-byte accesses on both sides, for X, BT and both leading dimensions 16-byte
+// aligned and K a multiple of 8: a thread loads 8 consecutive k of a token, the tile sits in LDS as
+// [token][k] with rows of 136 bytes (so that the column reads below spread over the banks), and a
+// thread gathers 8 consecutive tokens of one k for its store; 8 lanes write 128 contiguous bytes.
+__global__ void __launch_bounds__(256) transpose_tokens_wide_kernel(const uint16_t* __restrict__ X, int64_t ldx,
+                                                                    int64_t tokens, int64_t K,
+                                                                    uint16_t* __restrict__ BT, int64_t ldbt) {
+  constexpr int kPitch = 136;                      // bytes per token row in LDS
+  __shared__ __attribute__((aligned(16))) char tile[64 * kPitch];
+  const int64_t k0 = (int64_t)blockIdx.x * 64, tok0 = (int64_t)blockIdx.y * 64;
+  const int c = threadIdx.x & 7, r = threadIdx.x >> 3;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {                    // token r + 32j, k chunk c
+    const int64_t tok = tok0 + r + 32 * j, k = k0 + 8 * c;
+    uint4 w = make_uint4(0, 0, 0, 0);
+    if (tok < tokens && k < K) w = *reinterpret_cast<const uint4*>(X + tok * ldx + k);
+    uint2* dst = reinterpret_cast<uint2*>(tile + (r + 32 * j) * kPitch + c * 16);
+    dst[0] = make_uint2(w.x, w.y);
+    dst[1] = make_uint2(w.z, w.w);
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {                    // k row r + 32j, token chunk c
+    const int kr = r + 32 * j;
+    const int64_t k = k0 + kr, tok = tok0 + 8 * c;
+    uint32_t o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const uint32_t lo = *reinterpret_cast<const uint16_t*>(tile + (8 * c + 2 * e) * kPitch + kr * 2);
+      const uint32_t hi = *reinterpret_cast<const uint16_t*>(tile + (8 * c + 2 * e + 1) * kPitch + kr * 2);
+      o[e] = lo | (hi << 16);
+    }
+    if (k < K && tok < ldbt) *reinterpret_cast<uint4*>(BT + k * ldbt + tok) = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+}
+
 hipError_t launch_transpose_tokens(const uint16_t* X, int64_t ldx, int64_t tokens, int64_t K, uint16_t* BT, int64_t ldbt,
                                    hipStream_t st) {
   if (tokens == 0 || K == 0) return hipSuccess;
+  if (reinterpret_cast<uintptr_t>(X) % 16 == 0 && reinterpret_cast<uintptr_t>(BT) % 16 == 0 && ldx % 8 == 0 &&
+      ldbt % 8 == 0 && K % 8 == 0) {
+    hipLaunchKernelGGL(transpose_tokens_wide_kernel, dim3((unsigned)((K + 63) / 64), (unsigned)((ldbt + 63) / 64)), dim3(256),
+                       0, st, X, ldx, tokens, K, BT, ldbt);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(transpose_tokens_kernel, dim3((unsigned)((K + 63) / 64), (unsigned)((ldbt + 63) / 64)), dim3(256), 0,
                      st, X, ldx, tokens, K, BT, ldbt);
   return hipGetLastError();
