@@ -21,8 +21,8 @@
 //   * workgroups are persistent (one per compute unit): the k-steps of all tiles of a workgroup
 //     form one sequence, so the load pipeline runs on across tile boundaries while the consumers
 //     store their output;
-//   * each XCD (one L2 each) walks a contiguous range of the column-tile-major tile list and keeps
-//     its slab of B hot.
+//   * each XCD (one L2 each) walks a contiguous range of the column-tile-major tile list, so its
+//     workgroups share the gathered rows of one slab of B through that L2.
 #include <atomic>
 #include <type_traits>
 
@@ -119,8 +119,9 @@ __device__ __forceinline__ floatx16 smfmac(half8 a, half16 b, floatx16 c, int id
 // host sizes it) and every workgroup walks several tiles: starting a wide workgroup that owns most
 // of the LDS costs microseconds, and a persistent one can keep its load pipeline full across tile
 // boundaries.  Consecutive workgroup ids land on different XCDs; each XCD takes a contiguous
-// range of the column-tile-major list, so the workgroups of one XCD sweep the same slab of B at
-// the same time and it stays in that L2.
+// range of the column-tile-major list, so the workgroups of one XCD sweep the same slab of B and
+// a gathered row is fetched from beyond the L2 once for the workgroups that reach it while it is
+// resident (measured: all of them while the workgroups run in lock-step, fewer once they drift).
 struct TileWalk {
   int base, first, stride, count;
   __device__ __forceinline__ void locate(const SpmmParams& p, int t, int& ct, int& br) const {
