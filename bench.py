@@ -200,7 +200,7 @@ def main():
         D_d = torch.empty((R, C), dtype=torch.float16, device=dev)
         dense = lambda: torch.matmul(dense_A, B_d, out=D_d)
         n_dense = max(5, min(60, int(80.0 / max(dense_flop / 1.4e12, 1e-3)) + 1))   # about 80 ms of load (1.4 PFLOP/s assumed)
-        _, d_avg, d_med, _ = timed(dense, n_dense, max(2, args.warmup // 5))
+        _, d_avg = timed_region(dense, n_dense, max(2, args.warmup // 5))
         dense_entry = {"ms": round(d_avg, 5), "tflops": round(dense_flop / (d_avg * 1e-3) / 1e12, 2), "launches": n_dense,
                        "kind": "torch.matmul fp16 (hipBLASLt), same R x K x C, expanded masked A"}
         del D_d, dense_A
@@ -266,6 +266,8 @@ def main():
                                   "pseudo-random values; useful FLOP = half of the dense-equivalent count"},
     }
     out["hbm_calibration"] = hbm_cal
+    out["tables_timing"] = ("calls, configs and the dense comparators: W warm-up launches, then the stated number of launches "
+                            "back to back under one HIP event pair, time / launches (throughput, like the headline)")
     if dense_entry is not None:
         dense_entry["speedup_of_spmm"] = round(dense_entry["ms"] / ms_avg, 3)
         dense_entry["ideal_speedup"] = M / N
@@ -281,7 +283,7 @@ def main():
         calls = []
 
         def call_entry(name, fn, bytes_moved=None):
-            _, _, med, _ = timed(fn, n, 20)
+            _, med = timed_region(fn, n, 20)
             e = {"call": name, "ms": round(med, 5)}
             if bytes_moved is not None:
                 e.update({"algorithmic_bytes": int(bytes_moved), "GBs": round(bytes_moved / (med * 1e-3) / 1e9, 1),
@@ -308,7 +310,7 @@ def main():
         def compress_once():
             ws_keep.clear()
             ws_keep.append(binding.venom_compress(W_d, pruned[0], V, N, M))
-        _, _, c_med, _ = timed(compress_once, 10, 2)
+        _, c_med = timed_region(compress_once, 10, 2)
         cb = 3.0 * R * K + 2.0 * (4.5 * R * (K // M)) + 8.0 * (R // V) * (K // M)   # A + mask in, canonical + packed arrays out
         calls.append({"call": "venom_compress (dense + mask in, canonical and packed arrays out; one host round trip)",
                       "ms": round(c_med, 5), "algorithmic_bytes": int(cb), "GBs": round(cb / (c_med * 1e-3) / 1e9, 1),
@@ -329,7 +331,7 @@ def main():
             Rx, Kx, Cx = x["R"], x["K"], x["C"]
             Cx_d = torch.empty((Rx, Cx), dtype=torch.float16, device=dev)
             n = 100
-            _, avg, med, mn = timed(lambda: binding.venom_spmm(x["h"], x["B"], out=Cx_d), n, 100)
+            _, med = timed_region(lambda: binding.venom_spmm(x["h"], x["B"], out=Cx_d), n, 100)
             uf, ab, rf = rooflines(x, med)
             entry = {"workload": name, "R": Rx, "K": Kx, "C": Cx, "V": x["V"], "M": x["M"],
                      "ms_hot": round(med, 5), "useful_tflops": round(uf / (med * 1e-3) / 1e12, 2),
@@ -347,7 +349,7 @@ def main():
                 def cold_step():
                     i = state["i"] = (state["i"] + 1) % nrot
                     binding.venom_spmm(x["h"], Bs[i], out=Cs[i])
-                _, _, cmed, _ = timed(cold_step, n, 10)
+                _, cmed = timed_region(cold_step, n, 10)
                 _, _, crf = rooflines(x, cmed)
                 entry.update({"ms_cold": round(cmed, 5), "frac_cold": crf["frac"], "achieved_cold": crf["achieved"],
                               "cold_buffers": int(nrot)})
@@ -355,7 +357,7 @@ def main():
             if not args.no_dense:
                 dA = binding.venom_decompress(x["h"])
                 Dx = torch.empty((Rx, Cx), dtype=torch.float16, device=dev)
-                _, _, dmed, _ = timed(lambda: torch.matmul(dA, x["B"], out=Dx), 30, 5)
+                _, dmed = timed_region(lambda: torch.matmul(dA, x["B"], out=Dx), 30, 5)
                 entry.update({"dense_ms": round(dmed, 5), "speedup": round(dmed / med, 3), "ideal_speedup": x["M"] / N})
                 del dA, Dx
             table.append(entry)
