@@ -26,8 +26,9 @@ is stated on.  Prints ONE JSON line:
 
 Order of the GPU work: dense comparator, instruction probe, then 400 untimed launches of the
 product kernel (`settle_launches`: the GPU's power management needs about 25 ms of a new load to
-settle on a clock; the first launches run 10-20 % slower), then the W warm-up steps and the K timed
-steps.  The reported figure is therefore the throughput of a long-running job.
+settle on a clock; the very first launch is slow, the next few run about 10 % FASTER than the
+steady state), then the W warm-up steps and the K timed steps, launched back to back.  The reported
+figure is therefore the steady-state throughput of a long-running job.
 """
 from __future__ import annotations
 
@@ -225,9 +226,10 @@ def main():
 
     step = lambda: binding.venom_spmm(h, B_d, out=C_d, variant=args.variant)
     # The power management needs about a hundred launches (25 ms) of THIS kernel to settle on its
-    # clock: the first launches after any change of load run 10-20 % slower, whatever ran before.
-    # The figure of merit is the throughput of a long-running job, so the kernel runs untimed until
-    # then (reported as settle_launches); the W warm-up steps and the K timed steps follow directly.
+    # clock: the first launch after a change of load is slow, the next few are about 10 % faster than
+    # the steady state.  The figure of merit is the throughput of a long-running job, so the kernel
+    # runs untimed until then (reported as settle_launches); the W warm-up steps and the K timed
+    # steps follow directly.
     settle_launches = max(0, args.settle)
     for _ in range(settle_launches):
         step()
