@@ -82,6 +82,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="skip the table of the other workloads")
+    ap.add_argument("--calls-only", action="store_true", help="keep the table of the other entry points, skip the other workloads")
     ap.add_argument("--all-sweep-points", action="store_true",
                     help="the table holds all 36 points of the sparsity sweep (C = 256, 2048, 8192) instead of the C = 2048 column")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
@@ -348,7 +349,7 @@ def main():
         out["calls"] = calls
 
     # ------------------------------------------------------------------ the other workloads
-    if not args.no_configs and args.workload == "gpt3" and args.variant < 0:
+    if not args.no_configs and not args.calls_only and args.workload == "gpt3" and args.variant < 0:
         names = ["tiny", "bert_base", "bert_large"]
         sweep_c = inputs.SWEEP_C if args.all_sweep_points else (2048,)
         names += [f"sweep_v{v}_m{m}_c{c}" for c in sweep_c for v in inputs.SWEEP_V for m in inputs.SWEEP_M]
